@@ -1,0 +1,133 @@
+"""Float64 CPU oracle for one K-FAC step of one layer.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP library is checked against.  It is plain numpy in float64,
+written directly from the definitions, with no blocking, fusion or reordering, and it shares no
+code with the GPU path.  Only tests, the smoke check and the benchmark's CPU-baseline leg may
+import it; the product never does.
+
+What the path computes (every output is a unique real matrix, so the oracle is the definition
+itself, not an iteration):
+
+  * Kronecker factors of a layer's Fisher block, F ~ G (x) A (Sec. 3.2 "K-FAC", Eq. 5): A is the
+    mini-batch mean (Sec. 3.1, E[.] = mean over the mini-batch samples) of a a^T over the layer's
+    input vectors a, G the mean of g g^T over the gradients g of the loss w.r.t. the layer's
+    output.  For a convolution the "samples" are the unfolded input patches, one per image and
+    output position (the paper defers the conv case to Grosse & Martens 2016); a constant 1 is
+    appended to a when the layer has a bias.
+  * running average S <- rho S + (1 - rho) X of a factor (not in the paper; the usual K-FAC
+    convention, rho multiplies the old value);
+  * damping, Sec. 4.2 "Warmup damping" (its first equation): a multiple of the identity is
+    added before inverting.  For the Kronecker-factored block the damping gamma is split as
+    sqrt(gamma) on each factor;
+  * inverse of each damped factor, Eq. 6: (G (x) A)^-1 = G^-1 (x) A^-1;
+  * preconditioned gradient, Eq. 7: (G^-1 (x) A^-1) grad  ==  G^-1 . gradW . A^-1 for the weight
+    gradient gradW stored as a d_G x d_A matrix (rows = output channels).
+
+Parity pins (tests/test_oracle_pins.py) check every function against something other than
+itself: a brute-force loop unfold, torch's own unfold and autograd weight gradient, closed forms
+(trace identity, constant-input EMA, diagonal inverse), an explicitly formed Kronecker product, and
+the factor-memory totals the paper prints (Sec. 5.4, Fig. 4).  No function here is unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+ORDER_C_KH_KW = 0   # column (c, i, j) -> c*kh*kw + i*kw + j : matches weight.reshape(C_out, -1)
+ORDER_KH_KW_C = 1   # column (i, j, c) -> (i*kw + j)*C + c   : matches a channels-last weight
+
+
+def out_size(H: int, k: int, stride: int, pad: int) -> int:
+    return (H + 2 * pad - k) // stride + 1
+
+
+def unfold(act, kh: int, kw: int, stride: int, pad: int, order: int = ORDER_C_KH_KW) -> np.ndarray:
+    """Explicit patch matrix X (R x C*kh*kw) of a zero-padded input act[n, c, y, x].
+
+    Row r = (n*H_o + yo)*W_o + xo holds the patch read by output position (yo, xo) of image n:
+    entry (c, i, j) is act[n, c, yo*stride + i - pad, xo*stride + j - pad], 0 outside the image.
+    """
+    act = np.asarray(act, dtype=np.float64)
+    N, C, H, W = act.shape
+    Ho, Wo = out_size(H, kh, stride, pad), out_size(W, kw, stride, pad)
+    padded = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=np.float64)
+    padded[:, :, pad:pad + H, pad:pad + W] = act
+    X = np.empty((N, Ho, Wo, C, kh, kw), dtype=np.float64)
+    for i in range(kh):
+        for j in range(kw):
+            window = padded[:, :, i:i + (Ho - 1) * stride + 1:stride, j:j + (Wo - 1) * stride + 1:stride]
+            X[:, :, :, :, i, j] = window.transpose(0, 2, 3, 1)
+    if order == ORDER_C_KH_KW:
+        return X.reshape(N * Ho * Wo, C * kh * kw)
+    if order == ORDER_KH_KW_C:
+        return X.transpose(0, 1, 2, 4, 5, 3).reshape(N * Ho * Wo, kh * kw * C)
+    raise ValueError("unknown column order")
+
+
+def factor_A(act, kh: int, kw: int, stride: int, pad: int, has_bias: bool = True,
+             order: int = ORDER_C_KH_KW, scale: float | None = None) -> np.ndarray:
+    """A = scale * Xbar^T Xbar, Xbar = [unfold(act) | 1]; scale defaults to 1/R (mean over rows)."""
+    X = unfold(act, kh, kw, stride, pad, order)
+    if has_bias:
+        X = np.concatenate([X, np.ones((X.shape[0], 1))], axis=1)
+    s = 1.0 / X.shape[0] if scale is None else float(scale)
+    return (X.T @ X) * s
+
+
+def factor_G(gout, scale: float | None = None) -> np.ndarray:
+    """G = scale * Gamma^T Gamma, Gamma[(n, y, x), o] = gout[n, o, y, x]; scale defaults to 1/R."""
+    gout = np.asarray(gout, dtype=np.float64)
+    N, Co, Ho, Wo = gout.shape
+    Gamma = gout.transpose(0, 2, 3, 1).reshape(N * Ho * Wo, Co)
+    s = 1.0 / Gamma.shape[0] if scale is None else float(scale)
+    return (Gamma.T @ Gamma) * s
+
+
+def ema(running, fresh, decay: float) -> np.ndarray:
+    """S_new = decay * S_old + (1 - decay) * X."""
+    return float(decay) * np.asarray(running, dtype=np.float64) + (1.0 - float(decay)) * np.asarray(fresh, dtype=np.float64)
+
+
+def factor_damping(gamma: float) -> float:
+    """Per-factor diagonal shift for a block damping gamma: sqrt(gamma) on A and on G."""
+    return float(np.sqrt(gamma))
+
+
+def damped_inverse(S, damping: float) -> np.ndarray:
+    """(S + damping * I)^-1 for symmetric S."""
+    S = np.asarray(S, dtype=np.float64)
+    M = S + float(damping) * np.eye(S.shape[0])
+    return np.linalg.inv(M)
+
+
+def precondition(Ginv, gradW, Ainv) -> np.ndarray:
+    """P = Ginv . gradW . Ainv for a d_G x d_A weight gradient."""
+    return np.asarray(Ginv, dtype=np.float64) @ np.asarray(gradW, dtype=np.float64) @ np.asarray(Ainv, dtype=np.float64)
+
+
+def kfac_layer_step(act, gout, gradW, A_run, G_run, *, kh, kw, stride, pad, has_bias=True,
+                    order=ORDER_C_KH_KW, decay: float | None = 0.95, gamma: float = 1e-3):
+    """One K-FAC step of one layer, start to end.  decay=None skips the running average.
+
+    Returns a dict with every intermediate so that a test can compare stage by stage.
+    """
+    A_new = factor_A(act, kh, kw, stride, pad, has_bias, order)
+    G_new = factor_G(gout)
+    if decay is None:
+        A_s, G_s = A_new, G_new
+    else:
+        A_s, G_s = ema(A_run, A_new, decay), ema(G_run, G_new, decay)
+    lam = factor_damping(gamma)
+    A_inv = damped_inverse(A_s, lam)
+    G_inv = damped_inverse(G_s, lam)
+    P = precondition(G_inv, gradW, A_inv)
+    return dict(A_new=A_new, G_new=G_new, A_run=A_s, G_run=G_s, A_inv=A_inv, G_inv=G_inv, P=P)
+
+
+def factor_bytes(layers, bytes_per_el: int = 4) -> int:
+    """Bytes needed to hold every layer's A and G as full dense squares."""
+    return sum((l.d_A ** 2 + l.d_G ** 2) * bytes_per_el for l in layers)
+
+
+def packed_triangle_elems(n: int) -> int:
+    """Entries of the upper triangle of an n x n symmetric matrix (Sec. 3.4, symmetry-aware communication)."""
+    return n * (n + 1) // 2

@@ -1,0 +1,126 @@
+/*
+ * kfac.h -- C ABI of the MI355X (gfx950) K-FAC hot-path library.
+ *
+ * One K-FAC step of one conv/fc layer, as the per-GPU part of the distributed K-FAC optimizer
+ * (Algorithm 1: stages 1, 2, 4 and 5) computes it:
+ *
+ *   kfac_factor_A         A = E[a a^T]       Kronecker factor from the layer's input    (Sec. 3.2, Eq. 5; stage 1)
+ *   kfac_factor_G         G = E[g g^T]       Kronecker factor from the output gradient  (Sec. 3.2, Eq. 5; stage 2)
+ *   kfac_ema              S <- rho S + (1-rho) X   running average of a factor (standard K-FAC practice;
+ *                                                  the paper is silent on it)
+ *   kfac_damped_inverse   (S + lambda I)^-1  damping of Sec. 4.2 applied per factor, inverse of Eq. 6 (stage 4)
+ *   kfac_precondition     G^-1 gradW A^-1    = (G^-1 (x) A^-1) grad, Eq. 7                (stage 5)
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer unless its name ends in `_host`.  The caller owns every
+ *     buffer; the library allocates nothing, frees nothing and keeps no state between calls.
+ *     Scratch memory comes in through `ws` / `ws_bytes`; the *_workspace_bytes functions (pure
+ *     host functions) say how much a call needs.  `ws` must be 256-byte aligned.
+ *   - Matrices are dense, row-major, with leading dimension = number of columns, float32.
+ *     Symmetric outputs are written in full (both triangles) and are exactly symmetric.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work; they do not synchronise.  Buffers must stay valid until the stream has drained.
+ *   - Return value: KFAC_OK or a negative kfac_status.  Argument errors are detected on the host
+ *     before anything is launched.  Numerical failure of an inversion (matrix not positive
+ *     definite) is reported through the device-side `info` word, LAPACK potrf style.
+ *   - Thread safety: calls on different streams with disjoint buffers may run concurrently.
+ */
+#ifndef KFAC_H_
+#define KFAC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kfac_status {
+    KFAC_OK = 0,
+    KFAC_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent descriptor            */
+    KFAC_ERR_UNSUPPORTED = -2,   /* valid request this build has no kernel for                           */
+    KFAC_ERR_WORKSPACE = -3,     /* ws is NULL / misaligned / smaller than *_workspace_bytes says         */
+    KFAC_ERR_HIP = -4            /* a HIP runtime call (launch, memset) failed                            */
+} kfac_status;
+
+typedef enum kfac_dtype { KFAC_F32 = 0, KFAC_BF16 = 1, KFAC_F16 = 2 } kfac_dtype;
+
+/* Memory layout of activation / output-gradient tensors. Logical index is always (n, c, y, x). */
+typedef enum kfac_layout { KFAC_NCHW = 0, KFAC_NHWC = 1 } kfac_layout;
+
+/* Order of the unfolded-patch columns of A (and therefore of the columns of gradW):
+ *   KFAC_ORDER_C_KH_KW: column (c,i,j) = (c*kh + i)*kw + j   -- weight.reshape(C_out, -1) of an NCHW weight
+ *   KFAC_ORDER_KH_KW_C: column (i,j,c) = (i*kw + j)*C_in + c -- memory order of a channels-last weight; the
+ *                                                              fast path for NHWC tensors
+ * The bias column, when present, is the last one in both orders. */
+typedef enum kfac_col_order { KFAC_ORDER_C_KH_KW = 0, KFAC_ORDER_KH_KW_C = 1 } kfac_col_order;
+
+/* One conv or fully connected layer (fc: H = W = kh = kw = 1, stride 1, pad 0).
+ * Output size H_o = floor((H + 2 pad - kh)/stride) + 1, same for W.  R = N * H_o * W_o unfolded rows.
+ * d_A = C_in*kh*kw + has_bias, d_G = C_out. */
+typedef struct kfac_layer_desc {
+    int32_t N, C_in, H, W, C_out, kh, kw, stride, pad;
+    int32_t has_bias;   /* 1: append a constant-1 column to every unfolded row                           */
+    int32_t layout;     /* kfac_layout of act and gout                                                    */
+    int32_t dtype;      /* kfac_dtype of act and gout                                                     */
+    int32_t order;      /* kfac_col_order of A's rows/columns                                             */
+} kfac_layer_desc;
+
+enum { KFAC_OP_FACTOR_A = 0, KFAC_OP_FACTOR_G = 1 };
+
+const char* kfac_status_string(int status);
+
+/* Workspace a factor build needs (split-K partial tiles), op = KFAC_OP_FACTOR_A / _G.  0 on a bad descriptor. */
+size_t kfac_factor_workspace_bytes(int op, const kfac_layer_desc* desc);
+
+/* Stage 1.  A[d_A x d_A] = scale * sum_r abar_r abar_r^T over the R unfolded input patches abar_r of `act`
+ * (zero padding outside the image, a trailing 1 if has_bias); scale = 0 selects 1/R, the mini-batch
+ * mean of Sec. 3.1.  `act` holds N*C_in*H*W elements of desc->dtype in desc->layout.  Accumulation is fp32. */
+int kfac_factor_A(const kfac_layer_desc* desc, const void* act, float scale, float* A,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Stage 2.  G[d_G x d_G] = scale * sum_r g_r g_r^T over the R = N*H_o*W_o output positions, g_r the C_out-vector
+ * of `gout` (N*C_out*H_o*W_o elements, same dtype/layout as act) at that position; scale = 0 selects 1/R. */
+int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, float scale, float* G,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* running[dim x dim] <- decay * running + (1 - decay) * fresh, in place.  running and fresh must not overlap. */
+int kfac_ema(float* running, const float* fresh, int32_t dim, float decay, void* stream);
+
+/* Workspace for kfac_damped_inverse of one dim x dim matrix. */
+size_t kfac_inverse_workspace_bytes(int32_t dim);
+
+/* Minv[dim x dim] = (S + damping * I)^-1 for symmetric S (only S's lower triangle is read).  Sec. 4.2 / Eq. 6.
+ * S and Minv must not overlap.  *info (device int32, may be NULL) is set to 0 on success or to k > 0 when the
+ * leading minor of order k of the damped matrix is not positive definite; Minv is then unspecified. */
+int kfac_damped_inverse(const float* S, int32_t dim, float damping, float* Minv, int32_t* info,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* A batch of independent inversions advanced together (one launch per elimination step for the whole
+ * batch), for the many factors of a network.  items_host[i] and items_dev[i] describe the same matrix;
+ * items_dev is the device-resident copy the kernels read (the caller uploads it once, outside the step).
+ * Each item's `ws` needs kfac_inverse_workspace_bytes(dim) bytes of its own. */
+typedef struct kfac_inverse_item {
+    const float* S;     /* dim x dim symmetric input (device)                                             */
+    float* Minv;        /* dim x dim output (device)                                                      */
+    void* ws;           /* per-matrix scratch (device, 256-byte aligned)                                  */
+    int32_t* info;      /* device status word or NULL                                                     */
+    int32_t dim;
+    float damping;
+} kfac_inverse_item;
+
+int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, const kfac_inverse_item* items_dev,
+                                int32_t count, void* stream);
+
+/* Workspace for kfac_precondition (the d_A x d_G intermediate). */
+size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA);
+
+/* Stage 5.  out[dG x dA] = Ginv[dG x dG] * gradW[dG x dA] * Ainv[dA x dA]  (Eq. 7 written for the weight
+ * gradient as a matrix).  Ginv and Ainv are symmetric; out must not overlap the inputs. */
+int kfac_precondition(const float* Ginv, const float* Ainv, const float* gradW, int32_t dG, int32_t dA,
+                      float* out, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFAC_H_ */

@@ -1,0 +1,213 @@
+"""ctypes binding of the K-FAC C ABI (include/kfac.h).  Argument marshalling only.
+
+Every function here has the name and argument order of the C entry point it calls; tensors are
+torch device tensors used purely as owned device memory (``data_ptr()``), and the stream is torch's
+current HIP stream unless one is given.  Nothing is computed in Python, and there is no fallback:
+if the compiled library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from . import synth
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libkfac_hip.so")
+
+KFAC_OK = 0
+KFAC_ERR_INVALID_ARG, KFAC_ERR_UNSUPPORTED, KFAC_ERR_WORKSPACE, KFAC_ERR_HIP = -1, -2, -3, -4
+KFAC_F32, KFAC_BF16, KFAC_F16 = 0, 1, 2
+KFAC_NCHW, KFAC_NHWC = 0, 1
+KFAC_ORDER_C_KH_KW, KFAC_ORDER_KH_KW_C = 0, 1
+KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_ema",
+    "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
+    "kfac_precondition_workspace_bytes", "kfac_precondition",
+)
+
+
+class kfac_layer_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C_in", "H", "W", "C_out", "kh", "kw", "stride", "pad", "has_bias", "layout", "dtype", "order")]
+
+
+class kfac_inverse_item(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_void_p), ("Minv", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("info", ctypes.c_void_p),
+                ("dim", ctypes.c_int32), ("damping", ctypes.c_float)]
+
+
+class KfacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libkfac_hip.so (built by paper_1811_12019_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_1811_12019_amd.build). "
+            "There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_float
+    descp = ctypes.POINTER(kfac_layer_desc)
+    itemp = ctypes.POINTER(kfac_inverse_item)
+    lib.kfac_status_string.restype = ctypes.c_char_p
+    lib.kfac_status_string.argtypes = [ctypes.c_int]
+    lib.kfac_factor_workspace_bytes.restype = sz
+    lib.kfac_factor_workspace_bytes.argtypes = [ctypes.c_int, descp]
+    for name in ("kfac_factor_A", "kfac_factor_G"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [descp, vp, f32, vp, vp, sz, vp]
+    lib.kfac_ema.restype = ctypes.c_int
+    lib.kfac_ema.argtypes = [vp, vp, i32, f32, vp]
+    lib.kfac_inverse_workspace_bytes.restype = sz
+    lib.kfac_inverse_workspace_bytes.argtypes = [i32]
+    lib.kfac_damped_inverse.restype = ctypes.c_int
+    lib.kfac_damped_inverse.argtypes = [vp, i32, f32, vp, vp, vp, sz, vp]
+    lib.kfac_damped_inverse_batched.restype = ctypes.c_int
+    lib.kfac_damped_inverse_batched.argtypes = [itemp, vp, i32, vp]
+    lib.kfac_precondition_workspace_bytes.restype = sz
+    lib.kfac_precondition_workspace_bytes.argtypes = [i32, i32]
+    lib.kfac_precondition.restype = ctypes.c_int
+    lib.kfac_precondition.argtypes = [vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().kfac_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != KFAC_OK:
+        raise KfacError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+_TORCH_DTYPE = {KFAC_F32: torch.float32, KFAC_BF16: torch.bfloat16, KFAC_F16: torch.float16}
+
+
+def make_desc(shape: "synth.LayerShape", layout: int, dtype: int, order: int) -> kfac_layer_desc:
+    return kfac_layer_desc(shape.N, shape.C_in, shape.H, shape.W, shape.C_out, shape.kh, shape.kw, shape.stride,
+                           shape.pad, int(shape.has_bias), layout, dtype, order)
+
+
+def to_device_tensor(x_nchw, layout: int, dtype: int, device="cuda") -> torch.Tensor:
+    """Place a logical (n, c, y, x) array in device memory in the given layout and dtype (contiguous)."""
+    t = torch.as_tensor(x_nchw)
+    if layout == KFAC_NHWC:
+        t = t.permute(0, 2, 3, 1)
+    return t.contiguous().to(device=device, dtype=_TORCH_DTYPE[dtype]).contiguous()
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
+    """Device scratch of at least nbytes (torch's allocator hands out 512-byte aligned blocks)."""
+    if nbytes <= 0:
+        return None
+    return torch.empty(int(nbytes), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------------------------------------
+# entry points, same names as the C ABI
+# ------------------------------------------------------------------------------------------------
+def kfac_factor_workspace_bytes(op: int, desc: kfac_layer_desc) -> int:
+    return int(load_library().kfac_factor_workspace_bytes(op, ctypes.byref(desc)))
+
+
+def _factor(name: str, op: int, desc, x, scale, out, ws, stream):
+    lib = load_library()
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = getattr(lib, name)(ctypes.byref(desc), _ptr(x), float(scale), _ptr(out), _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, name)
+    return out
+
+
+def kfac_factor_A(desc: kfac_layer_desc, act: torch.Tensor, scale: float, A: torch.Tensor,
+                  ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _factor("kfac_factor_A", KFAC_OP_FACTOR_A, desc, act, scale, A, ws, stream)
+
+
+def kfac_factor_G(desc: kfac_layer_desc, gout: torch.Tensor, scale: float, G: torch.Tensor,
+                  ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _factor("kfac_factor_G", KFAC_OP_FACTOR_G, desc, gout, scale, G, ws, stream)
+
+
+def kfac_ema(running: torch.Tensor, fresh: torch.Tensor, dim: int, decay: float, stream=None) -> torch.Tensor:
+    _check(load_library().kfac_ema(_ptr(running), _ptr(fresh), int(dim), float(decay), _stream(stream)), "kfac_ema")
+    return running
+
+
+def kfac_inverse_workspace_bytes(dim: int) -> int:
+    return int(load_library().kfac_inverse_workspace_bytes(int(dim)))
+
+
+def kfac_damped_inverse(S: torch.Tensor, dim: int, damping: float, Minv: torch.Tensor,
+                        info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                        stream=None) -> torch.Tensor:
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().kfac_damped_inverse(_ptr(S), int(dim), float(damping), _ptr(Minv), _ptr(info), _ptr(ws),
+                                            ws_bytes, _stream(stream))
+    _check(rc, "kfac_damped_inverse")
+    return Minv
+
+
+class InverseBatch:
+    """Host + device copies of a kfac_inverse_item table (built once, reused every step)."""
+
+    def __init__(self, S: Sequence[torch.Tensor], Minv: Sequence[torch.Tensor], dampings: Sequence[float],
+                 info: Optional[torch.Tensor] = None, device="cuda"):
+        n = len(S)
+        dims = [int(s.shape[0]) for s in S]
+        self.order = sorted(range(n), key=lambda i: -dims[i])        # the ABI wants largest first
+        self.count = n
+        self.ws = [alloc_workspace(kfac_inverse_workspace_bytes(d), device) for d in dims]
+        self.info = info if info is not None else torch.zeros(n, dtype=torch.int32, device=device)
+        self.keep = (list(S), list(Minv))
+        arr = (kfac_inverse_item * n)()
+        for slot, i in enumerate(self.order):
+            arr[slot] = kfac_inverse_item(S[i].data_ptr(), Minv[i].data_ptr(), _ptr(self.ws[i]),
+                                          self.info.data_ptr() + 4 * i, dims[i], float(dampings[i]))
+        self.host = arr
+        raw = bytes(arr)
+        self.dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
+
+
+def kfac_damped_inverse_batched(batch: InverseBatch, stream=None) -> None:
+    rc = load_library().kfac_damped_inverse_batched(batch.host, batch.dev.data_ptr(), batch.count, _stream(stream))
+    _check(rc, "kfac_damped_inverse_batched")
+
+
+def kfac_precondition_workspace_bytes(dG: int, dA: int) -> int:
+    return int(load_library().kfac_precondition_workspace_bytes(int(dG), int(dA)))
+
+
+def kfac_precondition(Ginv: torch.Tensor, Ainv: torch.Tensor, gradW: torch.Tensor, dG: int, dA: int,
+                      out: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().kfac_precondition(_ptr(Ginv), _ptr(Ainv), _ptr(gradW), int(dG), int(dA), _ptr(out), _ptr(ws),
+                                          ws_bytes, _stream(stream))
+    _check(rc, "kfac_precondition")
+    return out

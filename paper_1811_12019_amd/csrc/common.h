@@ -1,0 +1,96 @@
+// Internal helpers shared by the gfx950 K-FAC kernels.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kfac.h"
+
+#define KFAC_HIP_TRY(expr)                         \
+    do {                                           \
+        hipError_t e__ = (expr);                   \
+        if (e__ != hipSuccess) return KFAC_ERR_HIP; \
+    } while (0)
+
+#define KFAC_LAUNCH_CHECK()                                     \
+    do {                                                        \
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP; \
+    } while (0)
+
+namespace kfac {
+
+constexpr int WAVE = 64;
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+// Four floats that are only guaranteed dword alignment (rows of an odd-sized matrix).
+struct __attribute__((packed, aligned(4))) f4u {
+    float x, y, z, w;
+};
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t b) {
+    _Float16 h;
+    __builtin_memcpy(&h, &b, 2);
+    return (float)h;
+}
+
+// Geometry of an implicit unfold: which input element feeds column `col` of unfolded row `r`.
+// factor_G uses the same structure with a 1x1 / stride 1 / no-bias geometry over the output tensor.
+struct Unfold {
+    int N, C, H, W;      // tensor being read (for G: C = C_out, H = H_o, W = W_o)
+    int Ho, Wo;          // rows: r = (n*Ho + yo)*Wo + xo
+    int kh, kw, stride, pad;
+    int has_bias;
+    int layout, dtype, order;
+    int R;               // N*Ho*Wo
+    int d;               // columns incl. the bias column
+};
+
+static inline bool make_unfold_A(const kfac_layer_desc* L, Unfold* u) {
+    if (!L) return false;
+    if (L->N <= 0 || L->C_in <= 0 || L->H <= 0 || L->W <= 0 || L->C_out <= 0 || L->kh <= 0 || L->kw <= 0 ||
+        L->stride <= 0 || L->pad < 0)
+        return false;
+    if (L->layout != KFAC_NCHW && L->layout != KFAC_NHWC) return false;
+    if (L->dtype != KFAC_F32 && L->dtype != KFAC_BF16 && L->dtype != KFAC_F16) return false;
+    if (L->order != KFAC_ORDER_C_KH_KW && L->order != KFAC_ORDER_KH_KW_C) return false;
+    if (L->has_bias != 0 && L->has_bias != 1) return false;
+    if (L->H + 2 * L->pad < L->kh || L->W + 2 * L->pad < L->kw) return false;
+    long long Ho = (L->H + 2 * L->pad - L->kh) / L->stride + 1;
+    long long Wo = (L->W + 2 * L->pad - L->kw) / L->stride + 1;
+    long long R = (long long)L->N * Ho * Wo;
+    long long d = (long long)L->C_in * L->kh * L->kw + L->has_bias;
+    long long in_elems = (long long)L->N * L->C_in * L->H * L->W;
+    long long out_elems = R * L->C_out;
+    if (R <= 0 || R > 0x7fffffffLL || d > 32768 || L->C_out > 32768) return false;
+    if (in_elems > 0x7fffffffLL || out_elems > 0x7fffffffLL) return false;   // 32-bit element offsets
+    u->N = L->N; u->C = L->C_in; u->H = L->H; u->W = L->W;
+    u->Ho = (int)Ho; u->Wo = (int)Wo;
+    u->kh = L->kh; u->kw = L->kw; u->stride = L->stride; u->pad = L->pad;
+    u->has_bias = L->has_bias;
+    u->layout = L->layout; u->dtype = L->dtype; u->order = L->order;
+    u->R = (int)R; u->d = (int)d;
+    return true;
+}
+
+static inline bool make_unfold_G(const kfac_layer_desc* L, Unfold* u) {
+    Unfold a;
+    if (!make_unfold_A(L, &a)) return false;
+    u->N = L->N; u->C = L->C_out; u->H = a.Ho; u->W = a.Wo;
+    u->Ho = a.Ho; u->Wo = a.Wo;
+    u->kh = 1; u->kw = 1; u->stride = 1; u->pad = 0;
+    u->has_bias = 0;
+    u->layout = L->layout; u->dtype = L->dtype; u->order = KFAC_ORDER_KH_KW_C;
+    u->R = a.R; u->d = L->C_out;
+    return true;
+}
+
+}  // namespace kfac

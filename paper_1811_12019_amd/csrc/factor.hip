@@ -1,0 +1,256 @@
+// Kronecker-factor builders: A = scale * Xbar^T Xbar and G = scale * Gamma^T Gamma (Sec. 3.2, Eq. 5;
+// Algorithm 1 stages 1 and 2) computed straight from the activation / output-gradient tensor.  The
+// unfolded patch matrix is never materialised: tiles of it are gathered on the fly into LDS.
+//
+// Two kernels:
+//   factor_generic_kernel  any layout / dtype / column order, fp32 FMA.  The fallback.
+//   (MFMA fast path for NHWC bf16 lives further down.)
+// Both enumerate only the lower-triangular tiles of the symmetric output and mirror them, and both
+// can split the R unfolded rows over several workgroups (deterministic two-pass reduction through
+// the caller's workspace, no float atomics).
+#include "common.h"
+
+namespace kfac {
+
+__device__ __forceinline__ float load_elem(const void* x, int dtype, int idx) {
+    if (dtype == KFAC_F32) return ((const float*)x)[idx];
+    uint16_t b = ((const uint16_t*)x)[idx];
+    return dtype == KFAC_BF16 ? bf16_bits_to_float(b) : half_bits_to_float(b);
+}
+
+// lower-triangular tile index -> (I, J), I >= J
+__device__ __forceinline__ void tri_decode(int t, int& I, int& J) {
+    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while ((i + 1) * (i + 2) / 2 <= t) ++i;
+    while (i * (i + 1) / 2 > t) --i;
+    I = i;
+    J = t - i * (i + 1) / 2;
+}
+
+// Column of the unfolded matrix -> (channel, tap row, tap column); kind: 0 data, 1 bias (constant 1), 2 padding (0)
+struct ColInfo {
+    int c, i, j, kind;
+};
+
+__device__ __forceinline__ ColInfo decode_col(const Unfold& u, int col) {
+    ColInfo ci;
+    ci.c = ci.i = ci.j = 0;
+    if (col >= u.d) {
+        ci.kind = 2;
+    } else if (u.has_bias && col == u.d - 1) {
+        ci.kind = 1;
+    } else {
+        ci.kind = 0;
+        if (u.order == KFAC_ORDER_C_KH_KW) {
+            int khw = u.kh * u.kw;
+            ci.c = col / khw;
+            int rem = col - ci.c * khw;
+            ci.i = rem / u.kw;
+            ci.j = rem - ci.i * u.kw;
+        } else {
+            int tap = col / u.C;
+            ci.c = col - tap * u.C;
+            ci.i = tap / u.kw;
+            ci.j = tap - ci.i * u.kw;
+        }
+    }
+    return ci;
+}
+
+constexpr int GT = 64;   // generic kernel: output tile edge
+constexpr int GK = 16;   // unfolded rows per LDS stage
+
+__global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const void* __restrict__ x, float scale,
+                                                             float* __restrict__ out, float* __restrict__ partial,
+                                                             int rows_per_split) {
+    __shared__ float As[GK][GT + 4];
+    __shared__ float Bs[GK][GT + 4];
+    __shared__ int rowN[GK], rowY[GK], rowX[GK];
+
+    const int t = threadIdx.x;
+    int I, J;
+    tri_decode(blockIdx.x, I, J);
+    const int split = blockIdx.y;
+    const int r_begin = split * rows_per_split;
+    const int r_end = min(u.R, r_begin + rows_per_split);
+
+    const int m = t & 63, kb = t >> 6;
+    const ColInfo ca = decode_col(u, I * GT + m);
+    const ColInfo cb = decode_col(u, J * GT + m);
+    const int tx = t & 15, ty = t >> 4;
+
+    float acc[4][4] = {};
+    for (int r0 = r_begin; r0 < r_end; r0 += GK) {
+        if (t < GK) {
+            int r = r0 + t;
+            if (r < r_end) {
+                int n = r / (u.Ho * u.Wo);
+                int rem = r - n * (u.Ho * u.Wo);
+                int yo = rem / u.Wo;
+                int xo = rem - yo * u.Wo;
+                rowN[t] = n;
+                rowY[t] = yo * u.stride - u.pad;
+                rowX[t] = xo * u.stride - u.pad;
+            } else {
+                rowN[t] = -1;
+                rowY[t] = 0;
+                rowX[t] = 0;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            int k = kb + 4 * e;
+            int n = rowN[k];
+            float va = 0.f, vb = 0.f;
+            if (n >= 0) {
+                {
+                    if (ca.kind == 1) va = 1.f;
+                    else if (ca.kind == 0) {
+                        int y = rowY[k] + ca.i, xx = rowX[k] + ca.j;
+                        if (y >= 0 && y < u.H && xx >= 0 && xx < u.W) {
+                            int idx = u.layout == KFAC_NHWC ? ((n * u.H + y) * u.W + xx) * u.C + ca.c
+                                                            : ((n * u.C + ca.c) * u.H + y) * u.W + xx;
+                            va = load_elem(x, u.dtype, idx);
+                        }
+                    }
+                }
+                if (I == J) vb = va;
+                else {
+                    if (cb.kind == 1) vb = 1.f;
+                    else if (cb.kind == 0) {
+                        int y = rowY[k] + cb.i, xx = rowX[k] + cb.j;
+                        if (y >= 0 && y < u.H && xx >= 0 && xx < u.W) {
+                            int idx = u.layout == KFAC_NHWC ? ((n * u.H + y) * u.W + xx) * u.C + cb.c
+                                                            : ((n * u.C + cb.c) * u.H + y) * u.W + xx;
+                            vb = load_elem(x, u.dtype, idx);
+                        }
+                    }
+                }
+            }
+            As[k][m] = va;
+            Bs[k][m] = vb;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a[q] = As[k][ty * 4 + q];
+                b[q] = Bs[k][tx * 4 + q];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[p][q] = fmaf(a[p], b[q], acc[p][q]);
+        }
+        __syncthreads();
+    }
+
+    if (gridDim.y == 1) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int row = I * GT + ty * 4 + p, col = J * GT + tx * 4 + q;
+                if (row < u.d && col < u.d) {
+                    float v = acc[p][q] * scale;
+                    out[(size_t)row * u.d + col] = v;
+                    if (I != J) out[(size_t)col * u.d + row] = v;
+                }
+            }
+    } else {
+        float* dst = partial + ((size_t)split * gridDim.x + blockIdx.x) * (GT * GT);
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dst[(ty * 4 + p) * GT + tx * 4 + q] = acc[p][q];
+    }
+}
+
+// Second pass of a split build: sum the per-split partial tiles in a fixed order, scale, write the tile and its mirror.
+template <int T>
+__global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restrict__ partial, int nsplit, int d,
+                                                            float scale, float* __restrict__ out) {
+    int I, J;
+    tri_decode(blockIdx.x, I, J);
+    const int ntiles = gridDim.x;
+    for (int e = blockIdx.y * 256 + threadIdx.x; e < T * T; e += gridDim.y * 256) {
+        int lr = e / T, lc = e - lr * T;
+        int row = I * T + lr, col = J * T + lc;
+        if (row >= d || col >= d) continue;
+        float s = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) s += partial[((size_t)sp * ntiles + blockIdx.x) * (T * T) + e];
+        s *= scale;
+        out[(size_t)row * d + col] = s;
+        if (I != J) out[(size_t)col * d + row] = s;
+    }
+}
+
+struct FactorPlan {
+    int tiles_dim;   // tiles per dimension
+    int ntiles;      // lower-triangular tiles
+    int nsplit;
+    int rows_per_split;
+    size_t ws_bytes;
+};
+
+static FactorPlan plan_generic(const Unfold& u) {
+    FactorPlan p;
+    p.tiles_dim = ceil_div(u.d, GT);
+    p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
+    int want = ceil_div(2048, p.ntiles);
+    int max_split = ceil_div(u.R, 4 * GK);
+    p.nsplit = want < 1 ? 1 : (want > max_split ? max_split : want);
+    if (p.nsplit < 1) p.nsplit = 1;
+    p.rows_per_split = ceil_div(ceil_div(u.R, p.nsplit), GK) * GK;
+    p.nsplit = ceil_div(u.R, p.rows_per_split);
+    p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * p.ntiles * GT * GT * sizeof(float) : 0;
+    return p;
+}
+
+static int run_factor(const Unfold& u, const void* x, float scale, float* out, void* ws, size_t ws_bytes,
+                      hipStream_t stream) {
+    if (!x || !out) return KFAC_ERR_INVALID_ARG;
+    if (scale == 0.f) scale = 1.0f / (float)u.R;
+    FactorPlan p = plan_generic(u);
+    if (p.ws_bytes > 0) {
+        if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
+    }
+    dim3 grid(p.ntiles, p.nsplit);
+    hipLaunchKernelGGL(factor_generic_kernel, grid, dim3(256), 0, stream, u, x, scale, out, (float*)ws,
+                       p.rows_per_split);
+    KFAC_LAUNCH_CHECK();
+    if (p.nsplit > 1) {
+        hipLaunchKernelGGL(factor_reduce_kernel<GT>, dim3(p.ntiles, 4), dim3(256), 0, stream, (const float*)ws,
+                           p.nsplit, u.d, scale, out);
+        KFAC_LAUNCH_CHECK();
+    }
+    return KFAC_OK;
+}
+
+}  // namespace kfac
+
+using namespace kfac;
+
+extern "C" size_t kfac_factor_workspace_bytes(int op, const kfac_layer_desc* desc) {
+    Unfold u;
+    bool ok = op == KFAC_OP_FACTOR_A ? make_unfold_A(desc, &u) : op == KFAC_OP_FACTOR_G ? make_unfold_G(desc, &u) : false;
+    if (!ok) return 0;
+    return align_up(plan_generic(u).ws_bytes, 256);
+}
+
+extern "C" int kfac_factor_A(const kfac_layer_desc* desc, const void* act, float scale, float* A, void* ws,
+                             size_t ws_bytes, void* stream) {
+    Unfold u;
+    if (!make_unfold_A(desc, &u)) return KFAC_ERR_INVALID_ARG;
+    return run_factor(u, act, scale, A, ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, float scale, float* G, void* ws,
+                             size_t ws_bytes, void* stream) {
+    Unfold u;
+    if (!make_unfold_G(desc, &u)) return KFAC_ERR_INVALID_ARG;
+    return run_factor(u, gout, scale, G, ws, ws_bytes, (hipStream_t)stream);
+}

@@ -1,0 +1,102 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol,
+sizes workspaces, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1811_12019_amd import binding as kb
+from paper_1811_12019_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kfac.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kfac_[a-z_A-Z]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kb.load_library()
+    names = declared_symbols()
+    assert set(names) == set(kb.EXPORTED_SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert kb.status_string(0) == "ok"
+    assert "argument" in kb.status_string(kb.KFAC_ERR_INVALID_ARG)
+    assert "workspace" in kb.status_string(kb.KFAC_ERR_WORKSPACE)
+
+
+def test_struct_sizes_match_header():
+    assert ctypes.sizeof(kb.kfac_layer_desc) == 13 * 4
+    assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8
+
+
+def test_workspace_sizes():
+    d = kb.make_desc(synth.config1(), kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+    for op in (kb.KFAC_OP_FACTOR_A, kb.KFAC_OP_FACTOR_G):
+        assert kb.kfac_factor_workspace_bytes(op, d) % 256 == 0
+    assert kb.kfac_factor_workspace_bytes(7, d) == 0
+    bad = kb.make_desc(synth.config1(), kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+    bad.stride = 0
+    assert kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_A, bad) == 0
+    assert kb.kfac_inverse_workspace_bytes(0) == 0
+    assert kb.kfac_inverse_workspace_bytes(64) > 0
+    assert kb.kfac_inverse_workspace_bytes(4609) >= (2 * 4609 * 128 + 128 * 128) * 4
+    assert kb.kfac_precondition_workspace_bytes(512, 4609) >= 512 * 4609 * 4
+    assert kb.kfac_precondition_workspace_bytes(-1, 5) == 0
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    lib = kb.load_library()
+    d = kb.make_desc(synth.config0(), kb.KFAC_NCHW, kb.KFAC_F32, kb.KFAC_ORDER_C_KH_KW)
+    fake = ctypes.c_void_p(0x1000)     # never dereferenced: every call below must fail validation first
+    assert lib.kfac_factor_A(ctypes.byref(d), None, 0.0, fake, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_factor_A(None, fake, 0.0, fake, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    bad = kb.make_desc(synth.config0(), kb.KFAC_NCHW, kb.KFAC_F32, kb.KFAC_ORDER_C_KH_KW)
+    bad.layout = 5
+    assert lib.kfac_factor_G(ctypes.byref(bad), fake, 0.0, fake, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    bad = kb.make_desc(synth.config0(), kb.KFAC_NCHW, kb.KFAC_F32, kb.KFAC_ORDER_C_KH_KW)
+    bad.kh = 30                        # kernel larger than the padded image
+    assert lib.kfac_factor_A(ctypes.byref(bad), fake, 0.0, fake, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    # a build that needs scratch but gets none
+    big = kb.make_desc(synth.config2(), kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+    assert kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_G, big) > 0
+    assert lib.kfac_factor_G(ctypes.byref(big), fake, 0.0, fake, None, 0, None) == kb.KFAC_ERR_WORKSPACE
+    assert lib.kfac_factor_G(ctypes.byref(big), fake, 0.0, fake, ctypes.c_void_p(0x1010), 1 << 40, None) == kb.KFAC_ERR_WORKSPACE
+
+    assert lib.kfac_ema(None, fake, 4, 0.95, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_ema(fake, fake, 4, 0.95, None) == kb.KFAC_ERR_INVALID_ARG          # overlap
+    assert lib.kfac_ema(fake, ctypes.c_void_p(0x9000), 4, 1.5, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_ema(fake, ctypes.c_void_p(0x9000), 0, 0.5, None) == kb.KFAC_ERR_INVALID_ARG
+
+    assert lib.kfac_damped_inverse(fake, 0, 0.1, ctypes.c_void_p(0x9000), None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse(fake, 8, 0.1, fake, None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG   # in place
+    assert lib.kfac_damped_inverse(fake, 300, 0.1, ctypes.c_void_p(0x90000), None, None, 0, None) == kb.KFAC_ERR_WORKSPACE
+
+    items = (kb.kfac_inverse_item * 2)()
+    items[0] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 64, 0.1)
+    items[1] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 300, 0.1)       # not sorted largest-first
+    assert lib.kfac_damped_inverse_batched(items, fake, 2, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse_batched(items, fake, 0, None) == kb.KFAC_ERR_INVALID_ARG
+
+    assert lib.kfac_precondition(fake, fake, fake, 4, 5, None, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_precondition(fake, fake, fake, 4, 5, ctypes.c_void_p(0x9000), None, 0, None) == kb.KFAC_ERR_WORKSPACE
+    assert lib.kfac_precondition(fake, fake, fake, 4, 5, fake, ctypes.c_void_p(0x9000), 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1811_12019_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith(".py"):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b|import_module\(.oracle|kfac_oracle", text, flags=re.M), \
+                    f"{f} reaches into the oracle"
+    ora = open(os.path.join(ROOT, "oracle", "kfac_oracle.py")).read()
+    assert "paper_1811_12019_amd" not in ora and "ctypes" not in ora

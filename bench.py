@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark: one K-FAC step for all 54 conv/fc layers of ResNet-50 at per-GPU batch 32 on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic activations / output gradients
+already resident in HBM: 108 Kronecker-factor builds (bf16 inputs, fp32 accumulate), 108 running-average
+updates, 108 damped inverses (fp32) and 54 preconditioning products (fp32).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 32] [--no-cpu-baseline]
+
+One GPU only: the per-GPU share of the paper's data-parallel step is what is measured; --gpus N>1 exits.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_1811_12019_amd import binding as kb        # noqa: E402
+from paper_1811_12019_amd import step as kstep        # noqa: E402
+from paper_1811_12019_amd import synth                # noqa: E402
+
+PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, TFLOP/s, GB/s
+
+
+def kernel_work(net: kstep.KfacNetworkStep):
+    """Algorithmic work of each kernel over ONE step of the whole network: (bound, peak, unit, amount)."""
+    shapes = [l.shape for l in net.layers]
+    dims = [d for s in shapes for d in (s.d_A, s.d_G)]
+    fac = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in shapes)
+    w = {
+        "inv_update_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops(d) for d in dims)),
+        "gemm_nt_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
+        "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s", fac),
+        "factor_mfma_kernel": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac),
+        "kfac::ema_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
+    }
+    return w
+
+
+def timed_steps(net, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def stage_times(net, reps=3):
+    """Milliseconds per stage (HIP events on the launch stream), averaged over `reps` steps."""
+    names = ["factors", "ema", "inverse", "precondition"]
+    fns = [net.build_factors, net.update_running, net.invert, net.precondition]
+    acc = dict.fromkeys(names, 0.0)
+    for _ in range(reps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)]
+        evs[0].record()
+        for i, fn in enumerate(fns):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        for i, n in enumerate(names):
+            acc[n] += evs[i].elapsed_time(evs[i + 1]) / reps
+    return acc
+
+
+def cpu_oracle_baseline(net, sample_names):
+    """The float64 oracle, as it stands, on a few layers of the same workload; scaled to a whole step by
+    algorithmic flops.  Reported baseline only."""
+    from oracle import kfac_oracle as ko
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+
+    def layer_flops(s):
+        return (kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) + kstep.inverse_flops(s.d_A) +
+                kstep.inverse_flops(s.d_G) + kstep.precondition_flops(s.d_G, s.d_A))
+
+    total = sum(layer_flops(l.shape) for l in net.layers)
+    sample = [l for l in net.layers if l.shape.name in sample_names]
+    sample_flops = sum(layer_flops(l.shape) for l in sample)
+    t_cpu = 0.0
+    for l in sample:
+        s = l.shape
+        act = l.act.float().permute(0, 3, 1, 2).cpu().numpy()
+        gout = l.gout.float().permute(0, 3, 1, 2).cpu().numpy()
+        gw = l.gradW.cpu().numpy()
+        t0 = time.perf_counter()
+        ko.kfac_layer_step(act, gout, gw, np.eye(s.d_A), np.eye(s.d_G), kh=s.kh, kw=s.kw, stride=s.stride, pad=s.pad,
+                           order=ko.ORDER_KH_KW_C, decay=net.decay, gamma=net.damping ** 2)
+        t_cpu += time.perf_counter() - t0
+    est_ms = t_cpu * 1e3 * total / sample_flops
+    return {"value": round(est_ms, 1), "unit": "ms/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 numpy oracle on layers {sorted(sample_names)} ({t_cpu:.1f} s measured, "
+                      f"{100 * sample_flops / total:.1f}% of the step's algorithmic flops), scaled to all 54 layers by flops"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the per-GPU K-FAC step on ONE GPU; this build has no multi-GPU path "
+              f"(got --gpus {args.gpus}).", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists).", file=sys.stderr)
+        sys.exit(3)
+    kb.load_library()
+
+    layers = synth.resnet50_layers(args.batch)
+    net = kstep.KfacNetworkStep(layers, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=0.95, gamma=1e-3, seed=0)
+    for _ in range(args.warmup):
+        net.step()
+    ms = timed_steps(net, args.steps)
+
+    stages = stage_times(net)
+    # per-kernel durations over `steps` more steps, HIP events around every launch on the launch stream
+    kb.kfac_kernel_timing_enable(True)
+    for _ in range(args.steps):
+        net.step()
+    torch.cuda.synchronize()
+    report = kb.kfac_kernel_timing_report()
+    kb.kfac_kernel_timing_enable(False)
+    infos = torch.stack([net.inv_batch.info]).cpu()
+    assert int(infos.abs().max()) == 0, "an inversion reported a non-positive-definite factor"
+
+    work = kernel_work(net)
+    per_kernel = {}
+    for name, (tot_ms, n) in report.items():
+        base = name.split("<")[0]
+        e = {"ms_per_step": round(tot_ms / args.steps, 4), "launches_per_step": n / args.steps,
+             "avg_launch_us": round(1e3 * tot_ms / n, 2)}
+        if base in work:
+            bound, peak, unit, amount = work[base]
+            rate = amount / (tot_ms / args.steps * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+            e.update({"bound": bound, "achieved": round(rate, 2), "peak": peak, "unit": unit, "frac": round(rate / peak, 4)})
+        per_kernel[name] = e
+    dominant = max(report, key=lambda k: report[k][0])
+    dom = per_kernel[dominant]
+    roofline = {"kernel": dominant, "bound": dom.get("bound"), "achieved": dom.get("achieved"), "peak": dom.get("peak"),
+                "unit": dom.get("unit"), "frac": dom.get("frac"), "traffic": None,
+                "avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"]}
+
+    fac_flops = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in layers)
+    out = {
+        "metric": "ResNet-50 K-FAC step ms/GPU @ batch 32; factor TFLOP/s & % MFMA peak",
+        "value": round(ms, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 factor inputs, f32 accumulate/inverse/precondition", "data": "synthetic",
+        "config": {"workload": f"resnet50_kfac_step_all54layers_batch{args.batch}", "per_gpu_batch": args.batch,
+                   "layers": len(layers), "decay": 0.95, "gamma": 1e-3, "inverse_every_step": True},
+        "stage_ms": {k: round(v, 3) for k, v in stages.items()},
+        "factor_tflops": round(fac_flops / (stages["factors"] * 1e-3) / 1e12, 2),
+        "factor_frac_of_bf16_mfma_peak": round(fac_flops / (stages["factors"] * 1e-3) / 1e12 / PEAK["mfma_bf16"], 4),
+        "roofline": roofline,
+        "kernels": per_kernel,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_oracle_baseline(
+            net, {"conv1", "layer1.0.conv2", "layer2.1.conv1", "layer3.1.conv2", "layer4.1.conv2", "fc"})
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -120,6 +120,14 @@ size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA);
 int kfac_precondition(const float* Ginv, const float* Ainv, const float* gradW, int32_t dG, int32_t dA,
                       float* out, void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement aid (for benchmarks; not one of the paper's operations).  While enabled, every kernel the
+ * library launches is bracketed by two HIP events on its stream.  kfac_kernel_timing_report waits for them
+ * and writes one text line per kernel into the HOST buffer: "<kernel name> <total ms> <launches>\n",
+ * NUL-terminated, then forgets them.  Returns KFAC_ERR_WORKSPACE if the buffer is too small.  Process-wide
+ * state, off by default; do not enable it inside a throughput measurement. */
+int kfac_kernel_timing_enable(int enable);
+int kfac_kernel_timing_report(char* buf_host, size_t buf_bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_ema",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition",
+    "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
 )
 
 
@@ -84,6 +85,10 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_precondition_workspace_bytes.argtypes = [i32, i32]
     lib.kfac_precondition.restype = ctypes.c_int
     lib.kfac_precondition.argtypes = [vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.kfac_kernel_timing_enable.restype = ctypes.c_int
+    lib.kfac_kernel_timing_enable.argtypes = [ctypes.c_int]
+    lib.kfac_kernel_timing_report.restype = ctypes.c_int
+    lib.kfac_kernel_timing_report.argtypes = [ctypes.c_char_p, sz]
     _lib = lib
     return lib
 
@@ -210,4 +215,19 @@ def kfac_precondition(Ginv: torch.Tensor, Ainv: torch.Tensor, gradW: torch.Tenso
     rc = load_library().kfac_precondition(_ptr(Ginv), _ptr(Ainv), _ptr(gradW), int(dG), int(dA), _ptr(out), _ptr(ws),
                                           ws_bytes, _stream(stream))
     _check(rc, "kfac_precondition")
+    return out
+
+
+def kfac_kernel_timing_enable(enable: bool) -> None:
+    _check(load_library().kfac_kernel_timing_enable(int(bool(enable))), "kfac_kernel_timing_enable")
+
+
+def kfac_kernel_timing_report() -> dict:
+    """{kernel name: (total milliseconds, launches)} since timing was enabled or last reported."""
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(load_library().kfac_kernel_timing_report(buf, len(buf)), "kfac_kernel_timing_report")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, ms, n = line.rsplit(" ", 2)
+        out[name] = (float(ms), int(n))
     return out

@@ -17,7 +17,22 @@
         if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP; \
     } while (0)
 
+// Launch `kernel` and return KFAC_ERR_HIP from the enclosing function if the launch is rejected.
+#define KFAC_LAUNCH(kernel, grid, block, stream, ...)                              \
+    do {                                                                           \
+        void* tok__ = nullptr;                                                     \
+        if (kfac::timing_enabled()) kfac::timing_begin(#kernel, stream, &tok__);   \
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);           \
+        if (tok__) kfac::timing_end(stream, tok__);                                \
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;                  \
+    } while (0)
+
 namespace kfac {
+
+// Opt-in per-kernel event timing (runtime.hip).
+bool timing_enabled();
+void timing_begin(const char* name, hipStream_t stream, void** token);
+void timing_end(hipStream_t stream, void* token);
 
 constexpr int WAVE = 64;
 

@@ -35,8 +35,7 @@ extern "C" int kfac_ema(float* running, const float* fresh, int32_t dim, float d
     if (!(fresh + n <= rb || rb + n <= fresh)) return KFAC_ERR_INVALID_ARG;   // overlap
     size_t blocks = (n + 1023) / 1024;
     if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(kfac::ema_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, running, fresh, n,
+    KFAC_LAUNCH(kfac::ema_kernel, dim3((unsigned)blocks), dim3(256), (hipStream_t)stream, running, fresh, n,
                        decay, 1.0f - decay);
-    KFAC_LAUNCH_CHECK();
     return KFAC_OK;
 }

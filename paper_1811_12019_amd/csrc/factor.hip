@@ -219,13 +219,11 @@ static int run_factor(const Unfold& u, const void* x, float scale, float* out, v
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
     }
     dim3 grid(p.ntiles, p.nsplit);
-    hipLaunchKernelGGL(factor_generic_kernel, grid, dim3(256), 0, stream, u, x, scale, out, (float*)ws,
+    KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, x, scale, out, (float*)ws,
                        p.rows_per_split);
-    KFAC_LAUNCH_CHECK();
     if (p.nsplit > 1) {
-        hipLaunchKernelGGL(factor_reduce_kernel<GT>, dim3(p.ntiles, 4), dim3(256), 0, stream, (const float*)ws,
+        KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, 4), dim3(256), stream, (const float*)ws,
                            p.nsplit, u.d, scale, out);
-        KFAC_LAUNCH_CHECK();
     }
     return KFAC_OK;
 }

@@ -294,8 +294,7 @@ static int run_group(const kfac_inverse_item* host, const kfac_inverse_item* dev
         b.count = n_multi;
         b.prefix[0] = 0;
         for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-        hipLaunchKernelGGL(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), 0, stream, b);
-        KFAC_LAUNCH_CHECK();
+        KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
     }
     for (int step = 0; step < max_steps; ++step) {
         int active = 0;   // multi-block matrices that still have a block `step`
@@ -307,21 +306,17 @@ static int run_group(const kfac_inverse_item* host, const kfac_inverse_item* dev
                 s.first = first + n_multi;
                 if (!dev) s.single = host[first + n_multi];
                 s.count = count - n_multi;
-                hipLaunchKernelGGL(inv_pivot_kernel, dim3(s.count), dim3(256), 0, stream, s, 0, 1);
-                KFAC_LAUNCH_CHECK();
+                KFAC_LAUNCH(inv_pivot_kernel, dim3(s.count), dim3(256), stream, s, 0, 1);
             }
         }
         if (active == 0) continue;
         b.count = active;
-        hipLaunchKernelGGL(inv_pivot_kernel, dim3(active), dim3(256), 0, stream, b, step, 0);
-        KFAC_LAUNCH_CHECK();
+        KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);
         b.prefix[0] = 0;
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
-        hipLaunchKernelGGL(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), 0, stream, b, step);
-        KFAC_LAUNCH_CHECK();
+        KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-        hipLaunchKernelGGL(inv_update_kernel, dim3(b.prefix[active]), dim3(256), 0, stream, b, step);
-        KFAC_LAUNCH_CHECK();
+        KFAC_LAUNCH(inv_update_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
     }
     return KFAC_OK;
 }

@@ -31,8 +31,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const float* __restrict__ 
 static int gemm_nt(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K,
                    hipStream_t stream) {
     dim3 grid(ceil_div(N, TM), ceil_div(M, TM));
-    hipLaunchKernelGGL(gemm_nt_kernel, grid, dim3(256), 0, stream, A, lda, B, ldb, C, ldc, M, N, K);
-    KFAC_LAUNCH_CHECK();
+    KFAC_LAUNCH(gemm_nt_kernel, grid, dim3(256), stream, A, lda, B, ldb, C, ldc, M, N, K);
     return KFAC_OK;
 }
 

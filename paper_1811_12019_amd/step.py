@@ -1,0 +1,127 @@
+"""Whole-network K-FAC step on one GPU: owns the device buffers of every layer and enqueues the C-ABI
+calls in the order of Algorithm 1 (stages 1, 2, 4, 5) for all layers locally.
+
+No arithmetic happens here: every number is produced by the HIP library.  torch is used for device
+memory, seeded synthetic inputs and the stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as kb
+from .synth import LayerShape, SIGMA_GOUT, SIGMA_GRADW
+
+
+def device_inputs(shape: LayerShape, seed: int, layer_idx: int, step: int, dtype: int, device="cuda"):
+    """Seeded synthetic (act, gout, gradW) generated on the device, NHWC memory order.
+
+    act/gout are returned as (N, H, W, C) tensors of the requested dtype; the logical (n, c, y, x) tensor
+    the definitions refer to is ``t.permute(0, 3, 1, 2)``.
+    """
+    g = torch.Generator(device=device)
+    g.manual_seed((seed * 1000003 + layer_idx) * 1000003 + step)
+    tdt = kb._TORCH_DTYPE[dtype]
+    act = torch.randn((shape.N, shape.H, shape.W, shape.C_in), generator=g, device=device, dtype=torch.float32)
+    if shape.relu_input:
+        act.clamp_(min=0)
+    gout = torch.randn((shape.N, shape.H_out, shape.W_out, shape.C_out), generator=g, device=device,
+                       dtype=torch.float32) * SIGMA_GOUT
+    gradw = torch.randn((shape.d_G, shape.d_A), generator=g, device=device, dtype=torch.float32) * SIGMA_GRADW
+    return act.to(tdt).contiguous(), gout.to(tdt).contiguous(), gradw.contiguous()
+
+
+class LayerState:
+    def __init__(self, shape: LayerShape, idx: int, dtype: int, order: int, seed: int, device):
+        self.shape = shape
+        self.desc = kb.make_desc(shape, kb.KFAC_NHWC, dtype, order)
+        self.act, self.gout, self.gradW = device_inputs(shape, seed, idx, 0, dtype, device)
+        dA, dG = shape.d_A, shape.d_G
+        f32 = dict(dtype=torch.float32, device=device)
+        self.A_new, self.G_new = torch.empty((dA, dA), **f32), torch.empty((dG, dG), **f32)
+        self.A_run, self.G_run = torch.eye(dA, **f32), torch.eye(dG, **f32)      # running averages start at I
+        self.A_inv, self.G_inv = torch.empty((dA, dA), **f32), torch.empty((dG, dG), **f32)
+        self.P = torch.empty((dG, dA), **f32)
+
+
+class KfacNetworkStep:
+    """All layers of a network resident on one GPU; step() = factor builds, running averages,
+    damped inverses (optionally skipped: stale inverses) and preconditioning for every layer."""
+
+    def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
+                 decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda"):
+        self.decay = decay
+        self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
+        self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
+        ws_f = max(max(kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_A, l.desc),
+                       kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_G, l.desc)) for l in self.layers)
+        ws_p = max(kb.kfac_precondition_workspace_bytes(l.shape.d_G, l.shape.d_A) for l in self.layers)
+        self.ws_factor = kb.alloc_workspace(ws_f, device)
+        self.ws_pre = kb.alloc_workspace(ws_p, device)
+        src = []
+        for l in self.layers:
+            src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
+        dst = []
+        for l in self.layers:
+            dst += [l.A_inv, l.G_inv]
+        self.inv_batch = kb.InverseBatch(src, dst, [self.damping] * len(src), device=device)
+
+    # -- stages ------------------------------------------------------------------------------
+    def build_factors(self, stream=None):
+        for l in self.layers:
+            kb.kfac_factor_A(l.desc, l.act, 0.0, l.A_new, self.ws_factor, stream)
+            kb.kfac_factor_G(l.desc, l.gout, 0.0, l.G_new, self.ws_factor, stream)
+
+    def update_running(self, stream=None):
+        if self.decay is None:
+            return
+        for l in self.layers:
+            kb.kfac_ema(l.A_run, l.A_new, l.shape.d_A, self.decay, stream)
+            kb.kfac_ema(l.G_run, l.G_new, l.shape.d_G, self.decay, stream)
+
+    def invert(self, stream=None):
+        kb.kfac_damped_inverse_batched(self.inv_batch, stream)
+
+    def precondition(self, stream=None):
+        for l in self.layers:
+            kb.kfac_precondition(l.G_inv, l.A_inv, l.gradW, l.shape.d_G, l.shape.d_A, l.P, self.ws_pre, stream)
+
+    def step(self, refresh_inverse: bool = True, stream=None):
+        self.build_factors(stream)
+        self.update_running(stream)
+        if refresh_inverse:
+            self.invert(stream)
+        self.precondition(stream)
+
+    def reset_running(self):
+        for l in self.layers:
+            l.A_run.copy_(torch.eye(l.shape.d_A, device=l.A_run.device))
+            l.G_run.copy_(torch.eye(l.shape.d_G, device=l.G_run.device))
+
+
+# Algorithmic work, for rooflines (2 flops per multiply-add; symmetric outputs counted as a triangle).
+def factor_flops(rows: int, dim: int) -> float:
+    return float(rows) * dim * (dim + 1)
+
+
+def inverse_flops(dim: int) -> float:
+    return float(dim) ** 3
+
+
+def precondition_flops(dG: int, dA: int) -> float:
+    return 2.0 * dG * dG * dA + 2.0 * dG * dA * dA
+
+
+INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
+
+
+def inverse_update_flops(dim: int) -> float:
+    """Flops of the rank-b updates of the blocked sweep (triangle of the part outside each pivot block)."""
+    total, k0 = 0.0, 0
+    while k0 < dim:
+        b = min(INVERSE_BLOCK, dim - k0)
+        rest = dim - b
+        total += float(rest) * (rest + 1) * b
+        k0 += b
+    return total if dim > INVERSE_BLOCK else 0.0

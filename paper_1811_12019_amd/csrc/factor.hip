@@ -3,12 +3,13 @@
 // unfolded patch matrix is never materialised: tiles of it are gathered on the fly into LDS.
 //
 // Two kernels:
+//   factor_mfma_kernel     NHWC bf16/fp16, (kh, kw, c) column order, C % 8 == 0: matrix cores (factor_mfma.h).
 //   factor_generic_kernel  any layout / dtype / column order, fp32 FMA.  The fallback.
-//   (MFMA fast path for NHWC bf16 lives further down.)
 // Both enumerate only the lower-triangular tiles of the symmetric output and mirror them, and both
 // can split the R unfolded rows over several workgroups (deterministic two-pass reduction through
 // the caller's workspace, no float atomics).
 #include "common.h"
+#include "factor_mfma.h"
 
 namespace kfac {
 
@@ -16,15 +17,6 @@ __device__ __forceinline__ float load_elem(const void* x, int dtype, int idx) {
     if (dtype == KFAC_F32) return ((const float*)x)[idx];
     uint16_t b = ((const uint16_t*)x)[idx];
     return dtype == KFAC_BF16 ? bf16_bits_to_float(b) : half_bits_to_float(b);
-}
-
-// lower-triangular tile index -> (I, J), I >= J
-__device__ __forceinline__ void tri_decode(int t, int& I, int& J) {
-    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((i + 1) * (i + 2) / 2 <= t) ++i;
-    while (i * (i + 1) / 2 > t) --i;
-    I = i;
-    J = t - i * (i + 1) / 2;
 }
 
 // Column of the unfolded matrix -> (channel, tap row, tap column); kind: 0 data, 1 bias (constant 1), 2 padding (0)
@@ -210,10 +202,69 @@ static FactorPlan plan_generic(const Unfold& u) {
     return p;
 }
 
+// The matrix-core kernel needs 16-byte channel vectors in (kh, kw, c) column order.
+static bool mfma_eligible(const Unfold& u) {
+    if (u.dtype != KFAC_BF16 && u.dtype != KFAC_F16) return false;
+    if (u.layout != KFAC_NHWC || (u.C & 7)) return false;
+    if (u.order != KFAC_ORDER_KH_KW_C && !(u.kh == 1 && u.kw == 1)) return false;
+    return true;
+}
+
+static FactorPlan plan_mfma(const Unfold& u) {
+    FactorPlan p;
+    p.tiles_dim = ceil_div(u.d, FT);
+    p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
+    int want = 768 / p.ntiles;
+    int max_split = u.R / (4 * FK);
+    int ns = want < max_split ? want : max_split;
+    if (ns < 1) ns = 1;
+    if (ns >= 8) ns = ns / 8 * 8;          // multiples of 8 keep a row range on one XCD
+    p.rows_per_split = ceil_div(ceil_div(u.R, ns), FK) * FK;
+    p.nsplit = ceil_div(u.R, p.rows_per_split);
+    p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * p.ntiles * FT * FT * sizeof(float) : 0;
+    return p;
+}
+
+template <bool PLAIN, bool F16>
+static int launch_mfma(const Unfold& u, const FactorPlan& p, const void* x, float scale, float* out, float* ws,
+                       hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)factor_mfma_kernel<PLAIN, F16>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, FACTOR_MFMA_LDS);
+        attr_set = true;
+    }
+    void* tok = nullptr;
+    if (timing_enabled()) timing_begin("factor_mfma_kernel", stream, &tok);
+    hipLaunchKernelGGL((factor_mfma_kernel<PLAIN, F16>), dim3(p.ntiles * p.nsplit), dim3(256), FACTOR_MFMA_LDS, stream,
+                       u, (const uint16_t*)x, scale, out, ws, p.rows_per_split, p.ntiles, p.nsplit);
+    if (tok) timing_end(stream, tok);
+    if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+    return KFAC_OK;
+}
+
 static int run_factor(const Unfold& u, const void* x, float scale, float* out, void* ws, size_t ws_bytes,
                       hipStream_t stream) {
     if (!x || !out) return KFAC_ERR_INVALID_ARG;
     if (scale == 0.f) scale = 1.0f / (float)u.R;
+    if (mfma_eligible(u) && ((uintptr_t)x & 15) == 0) {
+        FactorPlan p = plan_mfma(u);
+        if (p.ws_bytes > 0) {
+            if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
+        }
+        const bool plain = u.kh == 1 && u.kw == 1 && u.stride == 1 && u.pad == 0;
+        const bool f16 = u.dtype == KFAC_F16;
+        int rc = plain ? (f16 ? launch_mfma<true, true>(u, p, x, scale, out, (float*)ws, stream)
+                              : launch_mfma<true, false>(u, p, x, scale, out, (float*)ws, stream))
+                       : (f16 ? launch_mfma<false, true>(u, p, x, scale, out, (float*)ws, stream)
+                              : launch_mfma<false, false>(u, p, x, scale, out, (float*)ws, stream));
+        if (rc != KFAC_OK) return rc;
+        if (p.nsplit > 1) {
+            KFAC_LAUNCH(factor_reduce_kernel<FT>, dim3(p.ntiles, 16), dim3(256), stream, (const float*)ws, p.nsplit,
+                        u.d, scale, out);
+        }
+        return KFAC_OK;
+    }
     FactorPlan p = plan_generic(u);
     if (p.ws_bytes > 0) {
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
@@ -236,7 +287,9 @@ extern "C" size_t kfac_factor_workspace_bytes(int op, const kfac_layer_desc* des
     Unfold u;
     bool ok = op == KFAC_OP_FACTOR_A ? make_unfold_A(desc, &u) : op == KFAC_OP_FACTOR_G ? make_unfold_G(desc, &u) : false;
     if (!ok) return 0;
-    return align_up(plan_generic(u).ws_bytes, 256);
+    size_t a = plan_generic(u).ws_bytes;                       // either kernel may serve the call
+    size_t b = mfma_eligible(u) ? plan_mfma(u).ws_bytes : 0;
+    return align_up(a > b ? a : b, 256);
 }
 
 extern "C" int kfac_factor_A(const kfac_layer_desc* desc, const void* act, float scale, float* A, void* ws,

@@ -41,14 +41,6 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
     local = wg - b.prefix[lo];
 }
 
-__device__ __forceinline__ void tri_decode_i(int t, int& I, int& J) {
-    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((i + 1) * (i + 2) / 2 <= t) ++i;
-    while (i * (i + 1) / 2 > t) --i;
-    I = i;
-    J = t - i * (i + 1) / 2;
-}
-
 struct WsView {
     float* U;   // d_pad x NB : copy of the pivot block column before the step
     float* T;   // d_pad x NB : U . P
@@ -71,7 +63,7 @@ __global__ __launch_bounds__(256) void inv_init_kernel(Batch b) {
     const kfac_inverse_item it = get_item(b, m);
     const int d = it.dim;
     int I, J;
-    tri_decode_i(tile, I, J);
+    tri_decode(tile, I, J);
     if (tile == 0 && threadIdx.x == 0 && it.info) *it.info = 0;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     for (int r = ty; r < NB; r += 8) {
@@ -226,7 +218,7 @@ __global__ __launch_bounds__(256) void inv_update_kernel(Batch b, int step) {
     const kfac_inverse_item it = get_item(b, m);
     const int d = it.dim;
     int I, J;
-    tri_decode_i(tile, I, J);
+    tri_decode(tile, I, J);
     const int kb = step;
     if (I == kb && J == kb) return;
     const int k0 = step * NB;

@@ -92,9 +92,18 @@ SMALL_SHAPES = [
     (kb.KFAC_NCHW, kb.KFAC_F32, kb.KFAC_ORDER_C_KH_KW),
     (kb.KFAC_NCHW, kb.KFAC_F16, kb.KFAC_ORDER_KH_KW_C),
     (kb.KFAC_NHWC, kb.KFAC_F32, kb.KFAC_ORDER_KH_KW_C),
+    (kb.KFAC_NHWC, kb.KFAC_F16, kb.KFAC_ORDER_KH_KW_C),
 ])
 def test_factors_small_shapes(shape, layout, dtype, order):
     check_factor_pair(shape, layout, dtype, order, seed=1)
+
+
+@pytest.mark.parametrize("name", ["layer1.0.conv2", "layer2.0.downsample", "layer3.1.conv2", "layer4.0.conv1", "fc"])
+def test_factors_resnet_layers_full_size(name):
+    """Full-size ResNet-50 layers at batch 32 in the benchmark's launch configuration (NHWC bf16, (kh,kw,c) order):
+    3x3 with 100,352 rows (split over rows), strided 1x1 shortcut, 2305-dim 3x3, 1025-dim 1x1, fc."""
+    shp = {l.name: l for l in synth.resnet50_layers(32)}[name]
+    check_factor_pair(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C, seed=5)
 
 
 def test_factor_scale_argument():

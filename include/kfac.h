@@ -120,6 +120,22 @@ size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA);
 int kfac_precondition(const float* Ginv, const float* Ainv, const float* gradW, int32_t dG, int32_t dA,
                       float* out, void* ws, size_t ws_bytes, void* stream);
 
+/* The preconditioning of many layers as two launches over the tiles of all of them (one per product).
+ * items_host[i] / items_dev[i] describe the same layer (device copy uploaded once by the caller); each item's
+ * `ws` needs kfac_precondition_workspace_bytes(dG, dA) bytes of its own.  Listing layers with large dA first
+ * gives the best load balance. */
+typedef struct kfac_precond_item {
+    const float* Ginv;   /* dG x dG (device) */
+    const float* Ainv;   /* dA x dA (device) */
+    const float* gradW;  /* dG x dA (device) */
+    float* out;          /* dG x dA (device) */
+    void* ws;            /* per-layer scratch (device, 256-byte aligned) */
+    int32_t dG, dA;
+} kfac_precond_item;
+
+int kfac_precondition_batched(const kfac_precond_item* items_host, const kfac_precond_item* items_dev,
+                              int32_t count, void* stream);
+
 /* Measurement aid (for benchmarks; not one of the paper's operations).  While enabled, every kernel the
  * library launches is bracketed by two HIP events on its stream.  kfac_kernel_timing_report waits for them
  * and writes one text line per kernel into the HOST buffer: "<kernel name> <total ms> <launches>\n",

@@ -28,7 +28,7 @@ KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_ema",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
-    "kfac_precondition_workspace_bytes", "kfac_precondition",
+    "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
 )
 
@@ -41,6 +41,11 @@ class kfac_layer_desc(ctypes.Structure):
 class kfac_inverse_item(ctypes.Structure):
     _fields_ = [("S", ctypes.c_void_p), ("Minv", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("info", ctypes.c_void_p),
                 ("dim", ctypes.c_int32), ("damping", ctypes.c_float)]
+
+
+class kfac_precond_item(ctypes.Structure):
+    _fields_ = [("Ginv", ctypes.c_void_p), ("Ainv", ctypes.c_void_p), ("gradW", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("dG", ctypes.c_int32), ("dA", ctypes.c_int32)]
 
 
 class KfacError(RuntimeError):
@@ -85,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_precondition_workspace_bytes.argtypes = [i32, i32]
     lib.kfac_precondition.restype = ctypes.c_int
     lib.kfac_precondition.argtypes = [vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.kfac_precondition_batched.restype = ctypes.c_int
+    lib.kfac_precondition_batched.argtypes = [ctypes.POINTER(kfac_precond_item), vp, i32, vp]
     lib.kfac_kernel_timing_enable.restype = ctypes.c_int
     lib.kfac_kernel_timing_enable.argtypes = [ctypes.c_int]
     lib.kfac_kernel_timing_report.restype = ctypes.c_int
@@ -216,6 +223,30 @@ def kfac_precondition(Ginv: torch.Tensor, Ainv: torch.Tensor, gradW: torch.Tenso
                                           ws_bytes, _stream(stream))
     _check(rc, "kfac_precondition")
     return out
+
+
+class PrecondBatch:
+    """Host + device copies of a kfac_precond_item table (built once, reused every step)."""
+
+    def __init__(self, Ginv: Sequence[torch.Tensor], Ainv: Sequence[torch.Tensor], gradW: Sequence[torch.Tensor],
+                 out: Sequence[torch.Tensor], device="cuda"):
+        n = len(out)
+        shapes = [tuple(g.shape) for g in gradW]
+        self.order = sorted(range(n), key=lambda i: -shapes[i][1])       # large d_A first: best load balance
+        self.count = n
+        self.ws = [alloc_workspace(kfac_precondition_workspace_bytes(dG, dA), device) for dG, dA in shapes]
+        self.keep = (list(Ginv), list(Ainv), list(gradW), list(out))
+        arr = (kfac_precond_item * n)()
+        for slot, i in enumerate(self.order):
+            arr[slot] = kfac_precond_item(Ginv[i].data_ptr(), Ainv[i].data_ptr(), gradW[i].data_ptr(),
+                                          out[i].data_ptr(), self.ws[i].data_ptr(), shapes[i][0], shapes[i][1])
+        self.host = arr
+        self.dev = torch.frombuffer(bytearray(bytes(arr)), dtype=torch.uint8).to(device)
+
+
+def kfac_precondition_batched(batch: PrecondBatch, stream=None) -> None:
+    rc = load_library().kfac_precondition_batched(batch.host, batch.dev.data_ptr(), batch.count, _stream(stream))
+    _check(rc, "kfac_precondition_batched")
 
 
 def kfac_kernel_timing_enable(enable: bool) -> None:

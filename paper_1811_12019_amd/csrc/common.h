@@ -42,12 +42,21 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 
 // Four floats that are only guaranteed dword alignment (rows of an odd-sized matrix).
-struct __attribute__((packed, aligned(4))) f4u {
-    float x, y, z, w;
-};
+typedef v4f v4f_a4 __attribute__((aligned(4)));
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Pointers that kernels load from a descriptor table in memory have no known address space, and the compiler
+// would access them with flat instructions (slower, and they tie up the LDS wait counter as well).  Device code
+// that handles such pointers therefore uses pointers explicitly typed as global memory.
+#define KFAC_AS1 __attribute__((address_space(1)))
+typedef KFAC_AS1 float gfloat;
+typedef KFAC_AS1 int gint;
+template <class T>
+__device__ __forceinline__ KFAC_AS1 T* as_global(T* p) {
+    return (KFAC_AS1 T*)p;
+}
 
 // lower-triangular tile index -> (I, J), I >= J, tiles numbered row by row
 __device__ __forceinline__ void tri_decode(int t, int& I, int& J) {

@@ -161,22 +161,50 @@ __global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const voi
     }
 }
 
-// Second pass of a split build: sum the per-split partial tiles in a fixed order, scale, write the tile and its mirror.
+// Second pass of a split build: sum the per-split partial tiles in a fixed order, scale, write the tile and its
+// mirror.  One workgroup per 32 x 32 sub-block of a tile (grid.y of them per tile): every thread owns four
+// consecutive columns of one row, so partial reads are 128-byte runs; the mirror goes through an LDS transpose.
 template <int T>
 __global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restrict__ partial, int nsplit, int d,
                                                             float scale, float* __restrict__ out) {
+    __shared__ float tr[32][33];
     int I, J;
     tri_decode(blockIdx.x, I, J);
     const int ntiles = gridDim.x;
-    for (int e = blockIdx.y * 256 + threadIdx.x; e < T * T; e += gridDim.y * 256) {
-        int lr = e / T, lc = e - lr * T;
-        int row = I * T + lr, col = J * T + lc;
-        if (row >= d || col >= d) continue;
-        float s = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) s += partial[((size_t)sp * ntiles + blockIdx.x) * (T * T) + e];
+    constexpr int SB = T / 32;
+    const int si = blockIdx.y / SB, sj = blockIdx.y - si * SB;
+    const int lr = threadIdx.x >> 3, lc = (threadIdx.x & 7) * 4;
+    const int trow = si * 32 + lr, tcol = sj * 32 + lc;              // inside the tile
+    const int row = I * T + trow, col = J * T + tcol;
+    if (I * T + si * 32 >= d || J * T + sj * 32 >= d) return;       // whole sub-block outside the matrix
+    v4f s = {0.f, 0.f, 0.f, 0.f};
+    if (row < d && col < d) {
+        const float* src = partial + (size_t)blockIdx.x * (T * T) + trow * T + tcol;
+        const size_t stride = (size_t)ntiles * (T * T);
+        int sp = 0;
+        for (; sp + 4 <= nsplit; sp += 4) {
+            v4f a = *(const v4f*)(src + (size_t)sp * stride);
+            v4f b = *(const v4f*)(src + (size_t)(sp + 1) * stride);
+            v4f c = *(const v4f*)(src + (size_t)(sp + 2) * stride);
+            v4f e = *(const v4f*)(src + (size_t)(sp + 3) * stride);
+            s += a; s += b; s += c; s += e;
+        }
+        for (; sp < nsplit; ++sp) s += *(const v4f*)(src + (size_t)sp * stride);
         s *= scale;
-        out[(size_t)row * d + col] = s;
-        if (I != J) out[(size_t)col * d + row] = s;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (col + q < d) out[(size_t)row * d + col + q] = s[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) tr[lr][lc + q] = s[q];
+    if (I == J) return;                                              // uniform: diagonal tiles hold their own mirror
+    __syncthreads();
+    // transposed: thread (lr, lc..lc+3) now owns mirrored row (J*T + sj*32 + lr), columns I*T + si*32 + lc..+3
+    const int mrow = J * T + sj * 32 + lr, mcol = I * T + si * 32 + lc;
+    if (mrow < d) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (mcol + q < d) out[(size_t)mrow * d + mcol + q] = tr[lc + q][lr];
     }
 }
 
@@ -214,8 +242,8 @@ static FactorPlan plan_mfma(const Unfold& u) {
     FactorPlan p;
     p.tiles_dim = ceil_div(u.d, FT);
     p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
-    int want = 768 / p.ntiles;
-    int max_split = u.R / (4 * FK);
+    int want = 512 / p.ntiles;             // about two workgroups per CU
+    int max_split = u.R / (8 * FK);        // at least eight K-stages per workgroup
     int ns = want < max_split ? want : max_split;
     if (ns < 1) ns = 1;
     if (ns >= 8) ns = ns / 8 * 8;          // multiples of 8 keep a row range on one XCD
@@ -260,7 +288,7 @@ static int run_factor(const Unfold& u, const void* x, float scale, float* out, v
                               : launch_mfma<false, false>(u, p, x, scale, out, (float*)ws, stream));
         if (rc != KFAC_OK) return rc;
         if (p.nsplit > 1) {
-            KFAC_LAUNCH(factor_reduce_kernel<FT>, dim3(p.ntiles, 16), dim3(256), stream, (const float*)ws, p.nsplit,
+            KFAC_LAUNCH(factor_reduce_kernel<FT>, dim3(p.ntiles, (FT / 32) * (FT / 32)), dim3(256), stream, (const float*)ws, p.nsplit,
                         u.d, scale, out);
         }
         return KFAC_OK;
@@ -273,7 +301,7 @@ static int run_factor(const Unfold& u, const void* x, float scale, float* out, v
     KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, x, scale, out, (float*)ws,
                        p.rows_per_split);
     if (p.nsplit > 1) {
-        KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, 4), dim3(256), stream, (const float*)ws,
+        KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, (GT / 32) * (GT / 32)), dim3(256), stream, (const float*)ws,
                            p.nsplit, u.d, scale, out);
     }
     return KFAC_OK;

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void factor_mfma_kernel(Unfold u, const uint16
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int row = wm * 64 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = wn * 64 + q * 32 + lm;
-                    dst[row * FT + col] = acc[p][q][r];
+                    if (I * FT + row < u.d && J * FT + col < u.d) dst[row * FT + col] = acc[p][q][r];
                 }
         return;
     }

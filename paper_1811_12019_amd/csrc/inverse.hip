@@ -3,21 +3,28 @@
 //
 // Method: blocked symmetric sweep (block Gauss-Jordan without pivoting, which is safe for SPD matrices).
 // With the matrix cut into 128-wide blocks, eliminating block k does
-//     P        = W_kk^-1                       (one workgroup, register/LDS resident)
+//     P        = W_kk^-1                       (one workgroup, register resident)
 //     T        = W_:k P                        (panel, MFMA)
 //     W_ij    -= T_i W_jk^T   for i, j != k    (rank-128 update of the whole matrix, MFMA)
 //     W_:k = T, W_k: = T^T, W_kk = -P
-// and after all blocks W = -M^-1; the sign flip is folded into the last step.  Only tiles on or below the
-// diagonal are computed; each is mirrored, so W stays exactly symmetric.  Every step touches the full matrix,
-// so all steps expose the same, large amount of parallelism, and a batch of matrices of different sizes
+// and after all blocks W = -M^-1; the sign flip is folded into the last step.  Every step touches the whole
+// matrix, so all steps expose the same, large amount of parallelism, and a batch of matrices of different sizes
 // advances together: one launch per stage per step for the whole batch (the workgroup -> (matrix, tile) map is a
 // prefix table passed in the kernel arguments).
+//
+// Storage.  The sweep works on a copy W of the matrix in the caller's workspace whose rows are padded to a
+// multiple of 32 floats, so that every 128-wide tile row is a run of whole 128-byte lines, and it keeps only the
+// lower triangle (tiles on or below the diagonal) up to date: the part of block column k that lies above the
+// pivot block is read, transposed, from block row k.  Only the last step writes the caller's dense output, both
+// triangles, exactly symmetric (the upper one is a copy of the lower one).
 #include "gemm_f32.h"
 
 namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
 constexpr int MAXB = 120;        // matrices per launch group
+constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
+constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
 
 struct Batch {
     const kfac_inverse_item* table;   // device table, or nullptr -> `single`
@@ -27,8 +34,26 @@ struct Batch {
     int prefix[MAXB + 1];             // workgroup prefix sums over the active matrices
 };
 
-__device__ __forceinline__ kfac_inverse_item get_item(const Batch& b, int m) {
-    return b.table ? b.table[b.first + m] : b.single;
+// One matrix of the batch as the kernels see it: pointers typed as global memory.
+struct Item {
+    const gfloat* S;
+    gfloat* Minv;
+    gfloat* ws;
+    gint* info;
+    int dim;
+    float damping;
+};
+
+__device__ __forceinline__ Item get_item(const Batch& b, int m) {
+    const kfac_inverse_item raw = b.table ? b.table[b.first + m] : b.single;
+    Item it;
+    it.S = as_global(raw.S);
+    it.Minv = as_global(raw.Minv);
+    it.ws = as_global((float*)raw.ws);
+    it.info = as_global((int*)raw.info);
+    it.dim = raw.dim;
+    it.damping = raw.damping;
+    return it;
 }
 
 __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& local) {
@@ -41,60 +66,73 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
     local = wg - b.prefix[lo];
 }
 
+static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }
+static inline __host__ __device__ int ldw_of(int dim) { return (dim + 31) / 32 * 32; }
+
 struct WsView {
-    float* U;   // d_pad x NB : copy of the pivot block column before the step
-    float* T;   // d_pad x NB : U . P
-    float* P;   // NB x NB    : inverse of the pivot block
+    gfloat* W;   // dim x ldw : working copy, lower triangle maintained
+    int ldw;
+    gfloat* U;   // d_pad x NB : copy of block column k before the step (all rows, assembled from both triangles)
+    gfloat* T;   // d_pad x NB : U . P
+    gfloat* P;   // NB x NB    : inverse of the pivot block
 };
 
-__host__ __device__ inline WsView ws_view(void* ws, int dim) {
-    int d_pad = (dim + NB - 1) / NB * NB;
+__device__ inline WsView ws_view(gfloat* ws, int dim) {
+    const size_t d_pad = (size_t)nblk_of(dim) * NB;
     WsView v;
-    v.U = (float*)ws;
-    v.T = v.U + (size_t)d_pad * NB;
-    v.P = v.T + (size_t)d_pad * NB;
+    v.ldw = ldw_of(dim);
+    v.W = ws;
+    v.U = v.W + d_pad * v.ldw;
+    v.T = v.U + d_pad * NB;
+    v.P = v.T + d_pad * NB;
     return v;
 }
 
-// W = S + lambda I from S's lower triangle, written to both triangles; info = 0.
+// W(lower) = S(lower) + lambda I; info = 0.
 __global__ __launch_bounds__(256) void inv_init_kernel(Batch b) {
     int m, tile;
     locate(b, blockIdx.x, m, tile);
-    const kfac_inverse_item it = get_item(b, m);
+    const Item it = get_item(b, m);
     const int d = it.dim;
     int I, J;
     tri_decode(tile, I, J);
     if (tile == 0 && threadIdx.x == 0 && it.info) *it.info = 0;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
-    for (int r = ty; r < NB; r += 8) {
-        int row = I * NB + r;
-        if (row >= d) break;
-        for (int c = tx; c < NB; c += 32) {
-            int col = J * NB + c;
-            if (col >= d || col > row) continue;
-            float v = it.S[(size_t)row * d + col];
-            if (row == col) v += it.damping;
-            it.Minv[(size_t)row * d + col] = v;
-            if (row != col) it.Minv[(size_t)col * d + row] = v;
+    const WsView ws = ws_view(it.ws, d);
+    const gfloat* __restrict__ S = it.S;
+    const float lam = it.damping;
+    const int c = threadIdx.x & 127, rh = threadIdx.x >> 7;
+    const int col = J * NB + c;
+#pragma unroll 1
+    for (int r8 = 0; r8 < NB; r8 += 16) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = I * NB + r8 + 2 * i + rh;
+            v[i] = (row < d && col <= row) ? S[(size_t)row * d + col] + (row == col ? lam : 0.f) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = I * NB + r8 + 2 * i + rh;
+            if (row < d && col < ws.ldw) ws.W[(size_t)row * ws.ldw + col] = v[i];
         }
     }
 }
 
 // Inverse of the (at most 128 x 128) pivot block by an unblocked symmetric sweep held in registers:
 // thread (ti, tj) of a 16 x 16 grid owns entries (ti + 16a, tj + 16b), a, b = 0..7.
-__global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int write_from_S) {
+// from_S: single-block matrix, read S + lambda I and write the caller's output directly.
+__global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int from_S) {
     __shared__ float v[2][NB];
     __shared__ float sD[NB][NB + 1];
     __shared__ int bad;
     const int m = blockIdx.x;
-    const kfac_inverse_item it = get_item(b, m);
+    const Item it = get_item(b, m);
     const int d = it.dim;
     const int k0 = step * NB;
     const int nb = min(NB, d - k0);
     const bool last = k0 + NB >= d;
     const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
-    float* W = it.Minv;
-    WsView ws = ws_view(it.ws, d);
+    const WsView ws = ws_view(it.ws, d);
     if (t == 0) bad = 0;
 
     float D[8][8];
@@ -106,11 +144,11 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int w
             float x = (r == q) ? 1.f : 0.f;
             if (r < nb && q < nb) {
                 int hi = max(r, q), lo = min(r, q);
-                if (write_from_S) {
+                if (from_S) {
                     x = it.S[(size_t)(k0 + hi) * d + k0 + lo];
                     if (r == q) x += it.damping;
                 } else {
-                    x = W[(size_t)(k0 + hi) * d + k0 + lo];
+                    x = ws.W[(size_t)(k0 + hi) * ws.ldw + k0 + lo];
                 }
             }
             D[a][c] = x;
@@ -154,13 +192,13 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int w
     }
     __syncthreads();
     if (t == 0 && it.info) {
-        if (write_from_S) *it.info = bad;                       // single-block matrix: this is its only kernel
+        if (from_S) *it.info = bad;                             // single-block matrix: this is its only kernel
         else if (bad != 0) atomicCAS((int*)it.info, 0, bad);    // keep the first failing minor
     }
 
     // D now holds -P up to rounding asymmetry; take the lower triangle as the truth so that P is exactly
-    // symmetric.  The matrix gets -P (or +P on the last step, which folds in the final sign flip); the
-    // workspace gets +P for the panel product.
+    // symmetric.  The working copy gets -P; on the last step the caller's output gets +P (the final sign flip).
+    // The workspace gets +P for the panel product.
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
@@ -169,7 +207,6 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int w
             if (r >= q) sD[r][q] = D[a][c];
         }
     __syncthreads();
-    const float sgn = last ? -1.f : 1.f;
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
@@ -177,27 +214,34 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int w
             int r = ti + 16 * a, q = tj + 16 * c;
             if (r < nb && q < nb) {
                 float x = sD[max(r, q)][min(r, q)];
-                W[(size_t)(k0 + r) * d + k0 + q] = sgn * x;
-                if (!write_from_S) ws.P[r * NB + q] = -x;
+                if (last) it.Minv[(size_t)(k0 + r) * d + k0 + q] = -x;
+                else ws.W[(size_t)(k0 + r) * ws.ldw + k0 + q] = x;
+                if (!from_S) ws.P[r * NB + q] = -x;
             }
         }
 }
 
-// T = U . P for every 128-row slab of the pivot block column; U is copied aside for the update.
+// T = U . P for every 128-row slab of block column k; U is copied aside for the update.  Slabs below the pivot
+// block read the column block itself; slabs above it read block row k transposed.
 __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
     __shared__ float lds[GEMM_LDS_FLOATS];
     int m, slab;
     locate(b, blockIdx.x, m, slab);
-    const kfac_inverse_item it = get_item(b, m);
+    const Item it = get_item(b, m);
     const int d = it.dim;
     const int k0 = step * NB;
     const int nb = min(NB, d - k0);
     if (slab == step) return;                 // the pivot block's own rows are not needed
     const int r0 = slab * NB;
     const int rows = min(NB, d - r0);
-    WsView ws = ws_view(it.ws, d);
+    const WsView ws = ws_view(it.ws, d);
     TileAcc acc;
-    tile_mma_nt(it.Minv + (size_t)r0 * d + k0, d, rows, ws.P, NB, nb, nb, lds, acc, ws.U + (size_t)r0 * NB, NB);
+    if (slab > step)
+        tile_mma_nt<false>(ws.W + (size_t)r0 * ws.ldw + k0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc,
+                           ws.U + (size_t)r0 * NB, NB);
+    else
+        tile_mma_nt<true>(ws.W + (size_t)k0 * ws.ldw + r0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc,
+                          ws.U + (size_t)r0 * NB, NB);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -210,62 +254,166 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
             }
 }
 
-// Rank-nb update of every tile on or below the diagonal, mirrored; the pivot block row/column receive T.
+// One tile (I >= J) of one elimination step.  Tile kinds:
+//   regular      new = old - T_I U_J^T
+//   column       J == k, I > k:  new[a][c] = T[I*128 + a][c]          (block column k below the pivot)
+//   row          I == k, J < k:  new[a][c] = T[J*128 + c][a]          (block row k left of the pivot)
+// LAST = false: the tile goes back into the padded working copy (whole 512-byte rows).
+// LAST = true (the matrix's final step): the tile, negated, goes to the caller's output, and so does its mirror image.
+// Every tile passes through an LDS stage, 64 tile rows at a time, so that global accesses are row-wise.
+struct UpdCtx {
+    gfloat* W; int ldw; const gfloat* T; gfloat* out;
+    int d, i0, j0, irows, jrows, nb;
+    bool diag;
+};
+
+// stage (64 x sld floats) holds rows h0..h0+63 of the tile's new values (or of the product, for regular tiles
+// when COMBINE: new = old - stage, old prefetched in oldv).
+template <bool LAST, bool COMBINE>
+__device__ __forceinline__ void upd_flush(const UpdCtx& c, float* __restrict__ stage, int h0, const v4f (&oldv)[8]) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int pr = t >> 5, pc = (t & 31) * 4;
+    constexpr int sld = LAST ? SLD_T : SLD;
+    if constexpr (!LAST) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int rl = pr + 8 * p, row = h0 + rl;
+            if (row < c.irows && c.j0 + pc < c.ldw) {
+                v4f s = *(const v4f*)&stage[rl * sld + pc];
+                if constexpr (COMBINE) s = oldv[p] - s;
+                *(KFAC_AS1 v4f*)&c.W[(size_t)(c.i0 + row) * c.ldw + c.j0 + pc] = s;
+            }
+        }
+    } else {
+        // final values (sign flipped) back into the stage, then out: rows of the tile and rows of its mirror
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int rl = pr + 8 * p;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float x = stage[rl * sld + pc + i];
+                stage[rl * sld + pc + i] = COMBINE ? x - oldv[p][i] : -x;
+            }
+        }
+        __syncthreads();
+        // direct: wavefront w writes tile rows h0 + 16w .. +15, two 64-float runs per row
+        for (int rr = 0; rr < 16; ++rr) {
+            const int rl = wave * 16 + rr, row = h0 + rl;
+            if (row >= c.irows) break;
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                const int col = cc * 64 + lane;
+                if (col < c.jrows && !(c.diag && col > row))
+                    c.out[(size_t)(c.i0 + row) * c.d + c.j0 + col] = stage[rl * sld + col];
+            }
+        }
+        // mirror: wavefront w writes output rows j0 + 32w .. +31, one 64-float run (tile rows h0..h0+63) each
+        for (int cc = 0; cc < 32; ++cc) {
+            const int col = wave * 32 + cc, row = h0 + lane;
+            if (col >= c.jrows) break;
+            if (row < c.irows && !(c.diag && col >= row))
+                c.out[(size_t)(c.j0 + col) * c.d + c.i0 + row] = stage[lane * sld + col];
+        }
+    }
+}
+
+template <bool LAST>
+__device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __restrict__ U, float* __restrict__ lds) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int pr = t >> 5, pc = (t & 31) * 4;
+    constexpr int sld = LAST ? SLD_T : SLD;
+    TileAcc acc;
+    tile_mma_nt<false, 16>(c.T + (size_t)c.i0 * NB, NB, c.irows, U + (size_t)c.j0 * NB, NB, c.jrows, c.nb, lds, acc,
+                       nullptr, 0, c.diag);
+    const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int h0 = half * 64;
+        if (h0 >= c.irows) break;                          // uniform
+        if (half == 1) __syncthreads();                    // everyone is done with the first half's stage
+        v4f oldv[8];                                       // old values, fetched before anything is stored
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int row = h0 + pr + 8 * p;
+            v4f o = {0.f, 0.f, 0.f, 0.f};
+            if (row < c.irows && c.j0 + pc < c.ldw) o = *(const KFAC_AS1 v4f*)&c.W[(size_t)(c.i0 + row) * c.ldw + c.j0 + pc];
+            oldv[p] = o;
+        }
+        if (wm == half) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        lds[rl * sld + acc_col(wn, nbk, lane)] = dead ? 0.f : acc.c[mb][nbk][r];
+                    }
+        }
+        __syncthreads();
+        upd_flush<LAST, true>(c, lds, h0, oldv);
+    }
+}
+
+// column tile (from_rows = true): new[a][c] = T[(i0 + a)][c];  row tile: new[a][c] = T[(j0 + c)][a]
+template <bool LAST>
+__device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* __restrict__ lds) {
+    const int t = threadIdx.x;
+    const int pr = t >> 5, pc = (t & 31) * 4;
+    constexpr int sld = LAST ? SLD_T : SLD;
+    const v4f none[8] = {};
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int h0 = half * 64;
+        if (h0 >= c.irows) break;
+        if (half == 1) __syncthreads();
+        if (column) {
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int rl = pr + 8 * p, row = h0 + rl;
+                v4f x = {0.f, 0.f, 0.f, 0.f};
+                if (row < c.irows) x = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.i0 + row) * NB + pc];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds[rl * sld + pc + i] = pc + i < c.nb ? x[i] : 0.f;
+            }
+        } else {
+            const int ta = (t & 15) * 4, tc = t >> 4;     // 16 float4 along a (64 a's), 16 c's per pass
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int cc = tc + 16 * p;
+                v4f x = {0.f, 0.f, 0.f, 0.f};
+                if (cc < c.jrows) x = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.j0 + cc) * NB + h0 + ta];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds[(ta + i) * sld + cc] = h0 + ta + i < c.nb ? x[i] : 0.f;
+            }
+        }
+        __syncthreads();
+        upd_flush<LAST, false>(c, lds, h0, none);
+    }
+}
+
+template <bool LAST>
 __global__ __launch_bounds__(256) void inv_update_kernel(Batch b, int step) {
     __shared__ float lds[GEMM_LDS_FLOATS];
     int m, tile;
     locate(b, blockIdx.x, m, tile);
-    const kfac_inverse_item it = get_item(b, m);
-    const int d = it.dim;
+    const Item it = get_item(b, m);
     int I, J;
     tri_decode(tile, I, J);
     const int kb = step;
-    if (I == kb && J == kb) return;
-    const int k0 = step * NB;
-    const int nb = min(NB, d - k0);
-    const bool last = k0 + NB >= d;
-    const float sgn = last ? -1.f : 1.f;
-    float* W = it.Minv;
-    WsView ws = ws_view(it.ws, d);
-
-    if (I == kb || J == kb) {
-        // rows X0.. of the pivot column and their mirror in the pivot row
-        const int X = (I == kb) ? J : I;
-        const int x0 = X * NB;
-        const int rows = min(NB, d - x0);
-        const int c = threadIdx.x & 127, rh = threadIdx.x >> 7;
-        if (c < nb) {
-            for (int r = rh; r < rows; r += 2) {
-                float v = sgn * ws.T[(size_t)(x0 + r) * NB + c];
-                W[(size_t)(x0 + r) * d + k0 + c] = v;
-                W[(size_t)(k0 + c) * d + x0 + r] = v;
-            }
-        }
-        return;
-    }
-
-    const int i0 = I * NB, j0 = J * NB;
-    const int irows = min(NB, d - i0), jrows = min(NB, d - j0);
-    TileAcc acc;
-    tile_mma_nt(ws.T + (size_t)i0 * NB, NB, irows, ws.U + (size_t)j0 * NB, NB, jrows, nb, lds, acc);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                if (row >= irows || col >= jrows) continue;
-                if (I == J && col > row) continue;
-                size_t idx = (size_t)(i0 + row) * d + j0 + col;
-                float v = sgn * (W[idx] - acc.c[mb][nbk][r]);
-                W[idx] = v;
-                if (!(I == J && col == row)) W[(size_t)(j0 + col) * d + i0 + row] = v;
-            }
+    if (I == kb && J == kb) return;             // the pivot block itself was written by inv_pivot_kernel
+    const WsView ws = ws_view(it.ws, it.dim);
+    UpdCtx c;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T; c.out = it.Minv;
+    c.d = it.dim;
+    c.i0 = I * NB; c.j0 = J * NB;
+    c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
+    c.nb = min(NB, c.d - step * NB);
+    c.diag = I == J;
+    if (I != kb && J != kb) upd_regular<LAST>(c, ws.U, lds);
+    else upd_panel<LAST>(c, J == kb, lds);
 }
 
-static inline int nblk_of(int dim) { return (dim + NB - 1) / NB; }
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
 
 // items must be sorted by non-increasing dim (checked by the caller of this function).
@@ -288,29 +436,47 @@ static int run_group(const kfac_inverse_item* host, const kfac_inverse_item* dev
         for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
         KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
     }
+    if (count > n_multi) {
+        // single-block matrices: damp, invert and write in one kernel, straight from S
+        Batch s = b;
+        s.first = first + n_multi;
+        if (!dev) s.single = host[first + n_multi];
+        s.count = count - n_multi;
+        KFAC_LAUNCH(inv_pivot_kernel, dim3(s.count), dim3(256), stream, s, 0, 1);
+    }
     for (int step = 0; step < max_steps; ++step) {
         int active = 0;   // multi-block matrices that still have a block `step`
         while (active < n_multi && nblk_of(h[active].dim) > step) ++active;
-        if (step == 0) {
-            // single-block matrices: damp, invert and write in one kernel, straight from S
-            if (count > n_multi) {
-                Batch s = b;
-                s.first = first + n_multi;
-                if (!dev) s.single = host[first + n_multi];
-                s.count = count - n_multi;
-                KFAC_LAUNCH(inv_pivot_kernel, dim3(s.count), dim3(256), stream, s, 0, 1);
-            }
-        }
-        if (active == 0) continue;
+        if (active == 0) break;
         b.count = active;
         KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);
         b.prefix[0] = 0;
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
         KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
-        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-        KFAC_LAUNCH(inv_update_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
+        // matrices in their final step (they sit at the end of the active range) write the caller's output
+        int n_last = 0;
+        while (n_last < active && nblk_of(h[active - 1 - n_last].dim) == step + 1) ++n_last;
+        if (active > n_last) {
+            b.count = active - n_last;
+            for (int i = 0; i < b.count; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
+            KFAC_LAUNCH(inv_update_kernel<false>, dim3(b.prefix[b.count]), dim3(256), stream, b, step);
+        }
+        if (n_last > 0) {
+            Batch l = b;
+            l.first = first + active - n_last;
+            if (!dev) l.single = host[l.first];
+            l.count = n_last;
+            for (int i = 0; i < n_last; ++i) l.prefix[i + 1] = l.prefix[i] + tri_tiles(host[l.first + i].dim);
+            KFAC_LAUNCH(inv_update_kernel<true>, dim3(l.prefix[n_last]), dim3(256), stream, l, step);
+        }
     }
     return KFAC_OK;
+}
+
+static size_t ws_bytes_of(int dim) {
+    if (nblk_of(dim) == 1) return 256;
+    const size_t d_pad = (size_t)nblk_of(dim) * NB;
+    return align_up((d_pad * ldw_of(dim) + 2 * d_pad * NB + (size_t)NB * NB) * sizeof(float), 256);
 }
 
 static bool item_ok(const kfac_inverse_item& it) {
@@ -326,9 +492,7 @@ using namespace kfac;
 
 extern "C" size_t kfac_inverse_workspace_bytes(int32_t dim) {
     if (dim <= 0 || dim > 32768) return 0;
-    if (nblk_of(dim) == 1) return 256;
-    size_t d_pad = (size_t)nblk_of(dim) * NB;
-    return align_up((2 * d_pad * NB + (size_t)NB * NB) * sizeof(float), 256);
+    return ws_bytes_of(dim);
 }
 
 extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, float* Minv, int32_t* info,
@@ -337,7 +501,7 @@ extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, f
     it.S = S; it.Minv = Minv; it.ws = ws; it.info = info; it.dim = dim; it.damping = damping;
     if (dim <= 0 || dim > 32768 || !S || !Minv || S == Minv) return KFAC_ERR_INVALID_ARG;
     if (nblk_of(dim) > 1) {
-        if (!ws || ((uintptr_t)ws & 255) || ws_bytes < kfac_inverse_workspace_bytes(dim)) return KFAC_ERR_WORKSPACE;
+        if (!ws || ((uintptr_t)ws & 255) || ws_bytes < ws_bytes_of(dim)) return KFAC_ERR_WORKSPACE;
     }
     return run_group(&it, nullptr, 0, 1, (hipStream_t)stream);
 }

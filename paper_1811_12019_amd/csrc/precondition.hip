@@ -4,18 +4,43 @@
 // Both products run as "NT" tile products (both operands K-contiguous), using the symmetry of the inverses:
 //   Yt[dA x dG] = Ainv . gradW^T      Yt[j, i] = sum_k Ainv[j, k] gradW[i, k]
 //   P [dG x dA] = Ginv . Yt^T         P [i, j] = sum_k Ginv[i, k] Yt[j, k]
+// A batch of layers runs as two launches (one per product) over the tiles of all layers together, so that the
+// many small layers fill the machine; the workgroup -> (layer, tile) map is a prefix table in the kernel arguments.
 #include "gemm_f32.h"
 
 namespace kfac {
 
-// C[M x N] (ldc) = A[M x K] (lda) . B[N x K]^T (ldb)
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const float* __restrict__ A, int lda, const float* __restrict__ B,
-                                                      int ldb, float* __restrict__ C, int ldc, int M, int N, int K) {
+constexpr int PMAXB = 120;       // layers per launch group
+
+struct PBatch {
+    const kfac_precond_item* table;   // device table, or nullptr -> `single`
+    kfac_precond_item single;
+    int first, count;
+    int prefix[PMAXB + 1];            // workgroup prefix sums over the items of this launch
+};
+
+// phase 1: Yt[dA x dG] = Ainv . gradW^T      phase 2: out[dG x dA] = Ginv . Yt^T
+__global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     __shared__ float lds[GEMM_LDS_FLOATS];
-    const int i0 = blockIdx.y * TM, j0 = blockIdx.x * TM;
+    int lo = 0, hi = b.count;
+    const int wg = blockIdx.x;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (b.prefix[mid] <= wg) lo = mid; else hi = mid;
+    }
+    const kfac_precond_item it = b.table ? b.table[b.first + lo] : b.single;
+    const int local = wg - b.prefix[lo];
+    const gfloat *A, *B;
+    gfloat* C;
+    int M, N, K;
+    if (phase == 1) { A = as_global(it.Ainv); B = as_global(it.gradW); C = as_global((float*)it.ws); M = it.dA; N = it.dG; K = it.dA; }
+    else            { A = as_global(it.Ginv); B = as_global((const float*)it.ws); C = as_global(it.out); M = it.dG; N = it.dA; K = it.dG; }
+    const int tn = (N + TM - 1) / TM;
+    const int ti = local / tn, tj = local - ti * tn;
+    const int i0 = ti * TM, j0 = tj * TM;
     const int irows = min(TM, M - i0), jrows = min(TM, N - j0);
     TileAcc acc;
-    tile_mma_nt(A + (size_t)i0 * lda, lda, irows, B + (size_t)j0 * ldb, ldb, jrows, K, lds, acc);
+    tile_mma_nt(A + (size_t)i0 * K, K, irows, B + (size_t)j0 * K, K, jrows, K, lds, acc);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -24,15 +49,36 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const float* __restrict__ 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nb, lane);
-                if (row < irows && col < jrows) C[(size_t)(i0 + row) * ldc + j0 + col] = acc.c[mb][nb][r];
+                if (row < irows && col < jrows) C[(size_t)(i0 + row) * N + j0 + col] = acc.c[mb][nb][r];
             }
 }
 
-static int gemm_nt(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K,
-                   hipStream_t stream) {
-    dim3 grid(ceil_div(N, TM), ceil_div(M, TM));
-    KFAC_LAUNCH(gemm_nt_kernel, grid, dim3(256), stream, A, lda, B, ldb, C, ldc, M, N, K);
+static inline int tiles_of(int M, int N) { return ceil_div(M, TM) * ceil_div(N, TM); }
+
+static int run_group(const kfac_precond_item* host, const kfac_precond_item* dev, int first, int count,
+                     hipStream_t stream) {
+    PBatch b;
+    b.table = dev;
+    b.first = first;
+    b.count = count;
+    if (!dev) b.single = host[first];
+    for (int phase = 1; phase <= 2; ++phase) {
+        b.prefix[0] = 0;
+        for (int i = 0; i < count; ++i) {
+            const kfac_precond_item& it = host[first + i];
+            b.prefix[i + 1] = b.prefix[i] + (phase == 1 ? tiles_of(it.dA, it.dG) : tiles_of(it.dG, it.dA));
+        }
+        KFAC_LAUNCH(gemm_nt_kernel, dim3(b.prefix[count]), dim3(256), stream, b, phase);
+    }
     return KFAC_OK;
+}
+
+static bool item_ok(const kfac_precond_item& it) {
+    if (!it.Ginv || !it.Ainv || !it.gradW || !it.out || !it.ws) return false;
+    if (it.dG <= 0 || it.dA <= 0 || it.dG > 32768 || it.dA > 32768) return false;
+    if (it.out == it.gradW || it.out == it.Ginv || it.out == it.Ainv) return false;
+    if ((uintptr_t)it.ws & 255) return false;
+    return true;
 }
 
 }  // namespace kfac
@@ -49,10 +95,22 @@ extern "C" int kfac_precondition(const float* Ginv, const float* Ainv, const flo
     if (!Ginv || !Ainv || !gradW || !out || dG <= 0 || dA <= 0 || dG > 32768 || dA > 32768) return KFAC_ERR_INVALID_ARG;
     if (out == gradW || out == Ginv || out == Ainv) return KFAC_ERR_INVALID_ARG;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < kfac_precondition_workspace_bytes(dG, dA)) return KFAC_ERR_WORKSPACE;
-    float* Yt = (float*)ws;
-    int rc = gemm_nt(Ainv, dA, gradW, dA, Yt, dG, dA, dG, dA, (hipStream_t)stream);
-    if (rc != KFAC_OK) return rc;
-    return gemm_nt(Ginv, dG, Yt, dG, out, dA, dG, dA, dG, (hipStream_t)stream);
+    kfac_precond_item it;
+    it.Ginv = Ginv; it.Ainv = Ainv; it.gradW = gradW; it.out = out; it.ws = ws; it.dG = dG; it.dA = dA;
+    return run_group(&it, nullptr, 0, 1, (hipStream_t)stream);
+}
+
+extern "C" int kfac_precondition_batched(const kfac_precond_item* items_host, const kfac_precond_item* items_dev,
+                                         int32_t count, void* stream) {
+    if (!items_host || !items_dev || count <= 0) return KFAC_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        if (!item_ok(items_host[i])) return KFAC_ERR_INVALID_ARG;
+    for (int first = 0; first < count; first += PMAXB) {
+        int n = count - first < PMAXB ? count - first : PMAXB;
+        int rc = run_group(items_host, items_dev, first, n, (hipStream_t)stream);
+        if (rc != KFAC_OK) return rc;
+    }
+    return KFAC_OK;
 }
 
 extern "C" const char* kfac_status_string(int status) {

@@ -56,9 +56,9 @@ class KfacNetworkStep:
         self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
         ws_f = max(max(kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_A, l.desc),
                        kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_G, l.desc)) for l in self.layers)
-        ws_p = max(kb.kfac_precondition_workspace_bytes(l.shape.d_G, l.shape.d_A) for l in self.layers)
         self.ws_factor = kb.alloc_workspace(ws_f, device)
-        self.ws_pre = kb.alloc_workspace(ws_p, device)
+        self.pre_batch = kb.PrecondBatch([l.G_inv for l in self.layers], [l.A_inv for l in self.layers],
+                                         [l.gradW for l in self.layers], [l.P for l in self.layers], device=device)
         src = []
         for l in self.layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
@@ -84,8 +84,7 @@ class KfacNetworkStep:
         kb.kfac_damped_inverse_batched(self.inv_batch, stream)
 
     def precondition(self, stream=None):
-        for l in self.layers:
-            kb.kfac_precondition(l.G_inv, l.A_inv, l.gradW, l.shape.d_G, l.shape.d_A, l.P, self.ws_pre, stream)
+        kb.kfac_precondition_batched(self.pre_batch, stream)
 
     def step(self, refresh_inverse: bool = True, stream=None):
         self.build_factors(stream)

@@ -35,6 +35,7 @@ def test_status_strings():
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(kb.kfac_layer_desc) == 13 * 4
     assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8
+    assert ctypes.sizeof(kb.kfac_precond_item) == 5 * 8 + 8
 
 
 def test_workspace_sizes():
@@ -85,6 +86,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_damped_inverse_batched(items, fake, 2, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse_batched(items, fake, 0, None) == kb.KFAC_ERR_INVALID_ARG
 
+    pit = (kb.kfac_precond_item * 1)()
+    pit[0] = kb.kfac_precond_item(0x1000, 0x2000, 0x3000, 0x3000, 0x4000, 4, 5)      # out aliases gradW
+    assert lib.kfac_precondition_batched(pit, fake, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_precondition_batched(pit, None, 1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, None, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, ctypes.c_void_p(0x9000), None, 0, None) == kb.KFAC_ERR_WORKSPACE
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, fake, ctypes.c_void_p(0x9000), 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG

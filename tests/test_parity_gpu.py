@@ -263,6 +263,23 @@ def test_precondition(dG, dA):
     assert rel_fro(P, ref) < PRE_TOL, rel_fro(P, ref)
 
 
+def test_precondition_batched_matches_single_calls():
+    shapes = [(64, 65), (256, 577), (130, 129), (512, 1153), (16, 145)]
+    rng = np.random.default_rng(12)
+    Gi = [ko.damped_inverse(synth.random_spd(g, 20 + i), 0.05).astype(np.float32) for i, (g, a) in enumerate(shapes)]
+    Ai = [ko.damped_inverse(synth.random_spd(a, 30 + i), 0.05).astype(np.float32) for i, (g, a) in enumerate(shapes)]
+    Ws = [(rng.standard_normal(s) * synth.SIGMA_GRADW).astype(np.float32) for s in shapes]
+    dev = lambda xs: [torch.from_numpy(x).to(DEV) for x in xs]
+    Gt, At, Wt = dev(Gi), dev(Ai), dev(Ws)
+    Pt = [torch.full(s, float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+    batch = kb.PrecondBatch(Gt, At, Wt, Pt, device=DEV)
+    kb.kfac_precondition_batched(batch)
+    torch.cuda.synchronize()
+    for g, a, w, p in zip(Gi, Ai, Ws, Pt):
+        assert rel_fro(p.cpu().numpy(), ko.precondition(g, w, a)) < PRE_TOL
+        np.testing.assert_array_equal(p.cpu().numpy(), gpu_precondition(g, a, w))
+
+
 def test_precondition_operand_roles():
     """Non-symmetric stand-ins for the inverses would expose a swapped or transposed operand; the ABI takes
     symmetric ones, so use distinct symmetric matrices and a rectangular gradient."""

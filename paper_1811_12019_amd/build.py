@@ -19,7 +19,8 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False) -> str:
     """Compile every kernel source into one shared library; returns its path.  Raises on failure."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+    extra = os.environ.get("KFAC_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [hipcc] + HIPCC_FLAGS + extra + ["-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the gfx-only target feature and says so; that line is noise
     err = "\n".join(l for l in proc.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -23,8 +23,21 @@ namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
 constexpr int MAXB = 120;        // matrices per launch group
+#ifndef UPD_TK
+#define UPD_TK 16
+#endif
+#ifndef UPD_WAVES
+#define UPD_WAVES 3
+#endif
 constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
 constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
+
+#ifdef KFAC_TILE_TRACE
+__device__ unsigned long long g_trace[4096 * 16];
+#define TR(slot) do { if (!LAST && threadIdx.x == 0 && blockIdx.x < 4096) { if (g_trace[blockIdx.x * 16 + (slot)] == 0) g_trace[blockIdx.x * 16 + (slot)] = wall_clock64(); } } while (0)
+#else
+#define TR(slot) do { } while (0)
+#endif
 
 struct Batch {
     const kfac_inverse_item* table;   // device table, or nullptr -> `single`
@@ -118,12 +131,82 @@ __global__ __launch_bounds__(256) void inv_init_kernel(Batch b) {
     }
 }
 
-// Inverse of the (at most 128 x 128) pivot block by an unblocked symmetric sweep held in registers:
-// thread (ti, tj) of a 16 x 16 grid owns entries (ti + 16a, tj + 16b), a, b = 0..7.
+// ---- pivot block -----------------------------------------------------------------------------------------------
+// Inverse of the (at most 128 x 128) pivot block by a symmetric sweep in 16-wide sub-blocks.  The block D lives in
+// registers in MFMA accumulator layout (4 wavefronts x 64 x 64 quadrants); per sub-block j:
+//   1. the owners of D's columns j copy them to LDS (U16, 128 x 16);
+//   2. wavefront 0 inverts the 16 x 16 diagonal sub-block with a register sweep (quad broadcasts + bpermute);
+//   3. every thread computes its part of T16 = U16 . P16; the rows of the sub-block itself are set to -P16;
+//   4. D -= T16 . U16^T on the matrix cores (K = 16), then rows / columns j of D are overwritten with T16.
+// Padding with the identity makes ragged blocks (fewer than 128 rows) need no special cases.
+constexpr int PSB = 16;          // sub-block
+constexpr int PLD = 20;          // LDS row stride of the 16-wide panels (float4 aligned)
+
+__device__ __forceinline__ float quad_bcast(float x, int k) {   // value of lane (4*(lane/4) + k)
+    const int v = __float_as_int(x);
+    int r;
+    switch (k) {
+        case 0: r = __builtin_amdgcn_update_dpp(v, v, 0x00, 0xf, 0xf, false); break;
+        case 1: r = __builtin_amdgcn_update_dpp(v, v, 0x55, 0xf, 0xf, false); break;
+        case 2: r = __builtin_amdgcn_update_dpp(v, v, 0xAA, 0xf, 0xf, false); break;
+        default: r = __builtin_amdgcn_update_dpp(v, v, 0xFF, 0xf, 0xf, false); break;
+    }
+    return __int_as_float(r);
+}
+
+// One wavefront: Ps = inverse of the symmetric positive definite 16 x 16 block D16 (rows of Us), lower triangle
+// taken as the truth.  Lane (i = lane/4, g = lane%4) holds E[i][4g..4g+3].  Returns the 1-based index of the first
+// non-positive pivot, or 0.
+__device__ __forceinline__ int invert16_wave(const float* __restrict__ D16, int ld, float* __restrict__ Ps) {
+    const int lane = threadIdx.x & 63, i = lane >> 2, g = lane & 3;
+    float E[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int c = 4 * g + q;
+        E[q] = D16[max(i, c) * ld + min(i, c)];
+    }
+    int bad = 0;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const float vi = quad_bcast(E[s & 3], s >> 2);                                    // E(i, s)
+        const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vi), 4 * s));   // E(s, s)
+        if (!(p > 0.f) && bad == 0) bad = s + 1;
+        float ip = __builtin_amdgcn_rcpf(p);              // 1 ulp estimate + one Newton step: ample for a pivot
+        ip = ip * fmaf(-p, ip, 2.0f);
+        float vc[4];                                                                      // E(4g+q, s) = E(s, 4g+q)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            vc[q] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (4 * (4 * g + q)), __float_as_int(vi)));
+        const float wi = vi * ip;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) E[q] = fmaf(-wi, vc[q], E[q]);
+        if (g == (s >> 2)) E[s & 3] = wi;
+        if (i == s) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) E[q] = vc[q] * ip;
+            if (g == (s >> 2)) E[s & 3] = -ip;
+        }
+    }
+    // E = -P16 up to rounding asymmetry: publish, then re-read the lower triangle so that P16 is exactly symmetric
+#pragma unroll
+    for (int q = 0; q < 4; ++q) Ps[i * PLD + 4 * g + q] = -E[q];
+    float sym[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int c = 4 * g + q;
+        sym[q] = Ps[max(i, c) * PLD + min(i, c)];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) Ps[i * PLD + 4 * g + q] = sym[q];
+    return bad;
+}
+
 // from_S: single-block matrix, read S + lambda I and write the caller's output directly.
 __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int from_S) {
-    __shared__ float v[2][NB];
-    __shared__ float sD[NB][NB + 1];
+    __shared__ float sD[NB * (NB + 1)];
+    __shared__ __attribute__((aligned(16))) float Us[NB * PLD];
+    __shared__ __attribute__((aligned(16))) float Ts[NB * PLD];
+    __shared__ __attribute__((aligned(16))) float Ps[PSB * PLD];
     __shared__ int bad;
     const int m = blockIdx.x;
     const Item it = get_item(b, m);
@@ -131,63 +214,141 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
     const int k0 = step * NB;
     const int nb = min(NB, d - k0);
     const bool last = k0 + NB >= d;
-    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
     const WsView ws = ws_view(it.ws, d);
     if (t == 0) bad = 0;
 
-    float D[8][8];
+    // ---- load: lower triangle, row-wise, into sD; identity outside the block.  All loads are issued before the
+    //      first LDS store so that the block costs one memory round trip, not one per row group ----
+    {
+        const int c4 = (t & 31) * 4, r0 = t >> 5;        // 8 rows x 32 float4 per pass, 16 passes
+        const bool vec_ok = !from_S;                     // the padded working copy is 16-byte aligned, S need not be
+        v4f v[16];
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            int r = ti + 16 * a, q = tj + 16 * c;
-            float x = (r == q) ? 1.f : 0.f;
-            if (r < nb && q < nb) {
-                int hi = max(r, q), lo = min(r, q);
-                if (from_S) {
-                    x = it.S[(size_t)(k0 + hi) * d + k0 + lo];
-                    if (r == q) x += it.damping;
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + 8 * p;
+            v4f x = {0.f, 0.f, 0.f, 0.f};
+            if (row < nb && c4 <= row) {
+                if (vec_ok) {
+                    x = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4];
                 } else {
-                    x = ws.W[(size_t)(k0 + hi) * ws.ldw + k0 + lo];
+                    const gfloat* src = it.S + (size_t)(k0 + row) * d + k0 + c4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (c4 + i <= row) x[i] = src[i] + (c4 + i == row ? it.damping : 0.f);
                 }
             }
-            D[a][c] = x;
+            v[p] = x;
         }
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + 8 * p;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = c4 + i;
+                const bool in = row < nb && c <= row;
+                sD[row * (NB + 1) + c] = in ? v[p][i] : (row == c ? 1.f : 0.f);
+            }
+        }
+    }
     __syncthreads();
+    v16f acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
+                acc[mb][nbk][r] = sD[max(row, col) * (NB + 1) + min(row, col)];
+            }
 
-    int buf = 0;
+    const int trow = t >> 1, tc0 = (t & 1) * 8;      // T16: thread -> one row, 8 of the 16 columns
 #pragma unroll
-    for (int q8 = 0; q8 < 8; ++q8) {
-        for (int jj = 0; jj < 16; ++jj) {
-            const int j = q8 * 16 + jj;
-            if (j >= nb) break;
-            if (tj == jj) {
+    for (int jb = 0; jb < NB / PSB; ++jb) {
+        const int j0 = jb * PSB;
+        if (j0 >= nb) break;                         // uniform
+        constexpr int dummy = 0; (void)dummy;
+        const int own_w = jb >> 2;                   // wn (for columns) / wm (for rows) that owns sub-block jb
+        const int own_b = (jb >> 1) & 1;             // nbk / mb inside the quadrant
+        const int own_h = jb & 1;                    // which 16 of the block's 32
+        __syncthreads();                             // previous sub-step's readers of Us / Ts are done
+        // 1. U16 = D[:, j0 : j0+16]
+        if (wn == own_w && (lm >> 4) == own_h) {
 #pragma unroll
-                for (int a = 0; a < 8; ++a) v[buf][ti + 16 * a] = D[a][q8];
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Us[acc_row(wm, mb, r, lane) * PLD + (lm & 15)] = acc[mb][own_b][r];
+        }
+        __syncthreads();
+        // 2. P16
+        if (wave == 0) {
+            const int f = invert16_wave(Us + j0 * PLD, PLD, Ps);
+            if (f != 0 && lane == 0 && bad == 0) bad = k0 + j0 + f;
+        }
+        __syncthreads();
+        // 3. T16 = U16 . P16, rows of the sub-block replaced by -P16
+        {
+            float tv[8] = {};
+            const v4f* up = (const v4f*)&Us[trow * PLD];
+#pragma unroll
+            for (int k4 = 0; k4 < 4; ++k4) {
+                const v4f u = up[k4];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const v4f p0 = *(const v4f*)&Ps[(4 * k4 + kk) * PLD + tc0];
+                    const v4f p1 = *(const v4f*)&Ps[(4 * k4 + kk) * PLD + tc0 + 4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        tv[c] = fmaf(u[kk], p0[c], tv[c]);
+                        tv[4 + c] = fmaf(u[kk], p1[c], tv[4 + c]);
+                    }
+                }
             }
-            __syncthreads();
-            const float p = v[buf][j];
-            if (!(p > 0.f) && t == 0 && bad == 0) bad = k0 + j + 1;
-            const float ip = 1.0f / p;
-            float wi[8], vj[8];
+            if (trow >= j0 && trow < j0 + PSB) {
 #pragma unroll
-            for (int a = 0; a < 8; ++a) wi[a] = v[buf][ti + 16 * a] * ip;
-#pragma unroll
-            for (int c = 0; c < 8; ++c) vj[c] = v[buf][tj + 16 * c];
-#pragma unroll
-            for (int a = 0; a < 8; ++a)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) D[a][c] = fmaf(-wi[a], vj[c], D[a][c]);
-            if (tj == jj) {
-#pragma unroll
-                for (int a = 0; a < 8; ++a) D[a][q8] = wi[a];
+                for (int c = 0; c < 8; ++c) tv[c] = -Ps[(trow - j0) * PLD + tc0 + c];
             }
-            if (ti == jj) {
+            *(v4f*)&Ts[trow * PLD + tc0] = v4f{tv[0], tv[1], tv[2], tv[3]};
+            *(v4f*)&Ts[trow * PLD + tc0 + 4] = v4f{tv[4], tv[5], tv[6], tv[7]};
+        }
+        __syncthreads();
+        // 4. D -= T16 . U16^T  (lane (lm, h) takes k = 8s + 4h .. +3 of both operands), then the fix-ups
 #pragma unroll
-                for (int c = 0; c < 8; ++c) D[q8][c] = vj[c] * ip;
-                if (tj == jj) D[q8][q8] = -ip;
-            }
-            buf ^= 1;
+        for (int s2 = 0; s2 < 2; ++s2) {
+            v4f a[2], bb[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) a[mb] = *(const v4f*)&Ts[(wm * 64 + mb * 32 + lm) * PLD + 8 * s2 + 4 * h];
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk) bb[nbk] = *(const v4f*)&Us[(wn * 64 + nbk * 32 + lm) * PLD + 8 * s2 + 4 * h];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nbk = 0; nbk < 2; ++nbk)
+                        acc[mb][nbk] = __builtin_amdgcn_mfma_f32_32x32x2f32(-a[mb][i], bb[nbk][i], acc[mb][nbk], 0, 0, 0);
+        }
+        // columns j of D <- T16 (and -P16 on the sub-block's own rows)
+        if (wn == own_w && (lm >> 4) == own_h) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[mb][own_b][r] = Ts[acc_row(wm, mb, r, lane) * PLD + (lm & 15)];
+        }
+        // rows j of D <- T16^T
+        if (wm == own_w) {
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int r = own_h * 8 + r8;                    // registers holding rows 16*own_h .. +15 of block own_b
+                    const int rloc = (r8 >> 2) * 8 + h * 4 + (r8 & 3);   // row inside the sub-block
+                    acc[own_b][nbk][r] = Ts[acc_col(wn, nbk, lane) * PLD + rloc];
+                }
         }
     }
     __syncthreads();
@@ -200,25 +361,26 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
     // symmetric.  The working copy gets -P; on the last step the caller's output gets +P (the final sign flip).
     // The workspace gets +P for the panel product.
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            int r = ti + 16 * a, q = tj + 16 * c;
-            if (r >= q) sD[r][q] = D[a][c];
-        }
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
+                if (row >= col) sD[row * (NB + 1) + col] = acc[mb][nbk][r];
+            }
     __syncthreads();
-#pragma unroll
-    for (int a = 0; a < 8; ++a)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            int r = ti + 16 * a, q = tj + 16 * c;
-            if (r < nb && q < nb) {
-                float x = sD[max(r, q)][min(r, q)];
-                if (last) it.Minv[(size_t)(k0 + r) * d + k0 + q] = -x;
-                else ws.W[(size_t)(k0 + r) * ws.ldw + k0 + q] = x;
-                if (!from_S) ws.P[r * NB + q] = -x;
+    {
+        const int c = t & 127, rh = t >> 7;
+        if (c < nb) {
+            for (int row = rh; row < nb; row += 2) {
+                const float x = sD[max(row, c) * (NB + 1) + min(row, c)];
+                if (last) it.Minv[(size_t)(k0 + row) * d + k0 + c] = -x;
+                else ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c] = x;
+                if (!from_S) ws.P[row * NB + c] = -x;
             }
         }
+    }
 }
 
 // T = U . P for every 128-row slab of block column k; U is copied aside for the update.  Slabs below the pivot
@@ -323,15 +485,20 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
     const int pr = t >> 5, pc = (t & 31) * 4;
     constexpr int sld = LAST ? SLD_T : SLD;
     TileAcc acc;
-    tile_mma_nt<false, 16>(c.T + (size_t)c.i0 * NB, NB, c.irows, U + (size_t)c.j0 * NB, NB, c.jrows, c.nb, lds, acc,
-                       nullptr, 0, c.diag);
+    TR(1);
+    tile_mma_nt<false, UPD_TK>(c.T + (size_t)c.i0 * NB, NB, c.irows, U + (size_t)c.j0 * NB, NB, c.jrows, c.nb, lds, acc,
+                           nullptr, 0, c.diag);
     const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
+    TR(2);
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
         const int h0 = half * 64;
         if (h0 >= c.irows) break;                          // uniform
         if (half == 1) __syncthreads();                    // everyone is done with the first half's stage
-        v4f oldv[8];                                       // old values, fetched before anything is stored
+        TR(3 + 3 * half);
+        // old values of this half, all fetched before anything is stored (loads and stores go to the same array:
+        // interleaving them would serialise the memory round trips)
+        v4f oldv[8];
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
             const int row = h0 + pr + 8 * p;
@@ -351,7 +518,9 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
                     }
         }
         __syncthreads();
+        TR(4 + 3 * half);
         upd_flush<LAST, true>(c, lds, h0, oldv);
+        TR(5 + 3 * half);
     }
 }
 
@@ -393,8 +562,9 @@ __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* _
 }
 
 template <bool LAST>
-__global__ __launch_bounds__(256) void inv_update_kernel(Batch b, int step) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b, int step) {
     __shared__ float lds[GEMM_LDS_FLOATS];
+    TR(0);
     int m, tile;
     locate(b, blockIdx.x, m, tile);
     const Item it = get_item(b, m);
@@ -520,3 +690,9 @@ extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, 
     }
     return KFAC_OK;
 }
+
+#ifdef KFAC_TILE_TRACE
+extern "C" int kfac_debug_trace_read(unsigned long long* host, size_t n) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(kfac::g_trace), n * sizeof(unsigned long long)) == hipSuccess ? 0 : -4;
+}
+#endif

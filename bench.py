@@ -35,11 +35,20 @@ def kernel_work(net: kstep.KfacNetworkStep):
     shapes = [l.shape for l in net.layers]
     dims = [d for s in shapes for d in (s.d_A, s.d_G)]
     fac = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in shapes)
+
+    def is_plain(s):
+        return s.kh == 1 and s.kw == 1 and s.stride == 1 and s.pad == 0
+
+    mfma_ok = [s for s in shapes if s.C_in % 8 == 0]
+    fac_conv = sum(kstep.factor_flops(s.R, s.d_A) for s in mfma_ok if not is_plain(s))
+    fac_plain = (sum(kstep.factor_flops(s.R, s.d_A) for s in mfma_ok if is_plain(s)) +
+                 sum(kstep.factor_flops(s.R, s.d_G) for s in shapes))
     w = {
         "inv_update_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops(d) for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s", fac),
-        "factor_mfma_kernel": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac),
+        "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),
+        "factor_dma_kernel<plain>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_plain),
         "kfac::ema_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
     }
     return w
@@ -141,7 +150,7 @@ def main():
     work = kernel_work(net)
     per_kernel = {}
     for name, (tot_ms, n) in report.items():
-        base = name.split("<")[0]
+        base = name if name in work else name.split("<")[0]
         e = {"ms_per_step": round(tot_ms / args.steps, 4), "launches_per_step": n / args.steps,
              "avg_launch_us": round(1e3 * tot_ms / n, 2)}
         if base in work:

@@ -84,6 +84,23 @@ int kfac_factor_A(const kfac_layer_desc* desc, const void* act, float scale, flo
 int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, float scale, float* G,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* Many factor builds at once (all layers of a network): builds that the matrix-core kernel can serve share a
+ * launch, so that the many small ones fill the machine together.  items_host[i] / items_dev[i] describe the same
+ * build (device copy uploaded once by the caller); each item's `ws` needs kfac_factor_workspace_bytes(op, &desc)
+ * bytes of its own.  Results are identical to the single calls. */
+typedef struct kfac_factor_item {
+    kfac_layer_desc desc;
+    const void* x;       /* act (op = KFAC_OP_FACTOR_A) or gout (op = KFAC_OP_FACTOR_G), device */
+    float* out;          /* d x d factor, device */
+    void* ws;            /* per-build scratch (device, 256-byte aligned) or NULL if none is needed */
+    size_t ws_bytes;
+    float scale;         /* 0 selects 1/R */
+    int32_t op;
+} kfac_factor_item;
+
+int kfac_factor_batched(const kfac_factor_item* items_host, const kfac_factor_item* items_dev, int32_t count,
+                        void* stream);
+
 /* running[dim x dim] <- decay * running + (1 - decay) * fresh, in place.  running and fresh must not overlap. */
 int kfac_ema(float* running, const float* fresh, int32_t dim, float decay, void* stream);
 

@@ -26,7 +26,8 @@ KFAC_ORDER_C_KH_KW, KFAC_ORDER_KH_KW_C = 0, 1
 KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_ema",
+    "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
+    "kfac_ema",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -36,6 +37,11 @@ EXPORTED_SYMBOLS = (
 class kfac_layer_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("N", "C_in", "H", "W", "C_out", "kh", "kw", "stride", "pad", "has_bias", "layout", "dtype", "order")]
+
+
+class kfac_factor_item(ctypes.Structure):
+    _fields_ = [("desc", kfac_layer_desc), ("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t), ("scale", ctypes.c_float), ("op", ctypes.c_int32)]
 
 
 class kfac_inverse_item(ctypes.Structure):
@@ -78,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [descp, vp, f32, vp, vp, sz, vp]
+    lib.kfac_factor_batched.restype = ctypes.c_int
+    lib.kfac_factor_batched.argtypes = [ctypes.POINTER(kfac_factor_item), vp, i32, vp]
     lib.kfac_ema.restype = ctypes.c_int
     lib.kfac_ema.argtypes = [vp, vp, i32, f32, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
@@ -165,6 +173,30 @@ def kfac_factor_A(desc: kfac_layer_desc, act: torch.Tensor, scale: float, A: tor
 def kfac_factor_G(desc: kfac_layer_desc, gout: torch.Tensor, scale: float, G: torch.Tensor,
                   ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     return _factor("kfac_factor_G", KFAC_OP_FACTOR_G, desc, gout, scale, G, ws, stream)
+
+
+class FactorBatch:
+    """Host + device copies of a kfac_factor_item table (built once, reused every step).
+
+    builds: sequence of (op, desc, x tensor, out tensor, scale)."""
+
+    def __init__(self, builds, device="cuda"):
+        n = len(builds)
+        self.count = n
+        self.ws = [alloc_workspace(kfac_factor_workspace_bytes(op, desc), device) for op, desc, _, _, _ in builds]
+        self.keep = list(builds)
+        arr = (kfac_factor_item * n)()
+        for i, (op, desc, x, out, scale) in enumerate(builds):
+            ws = self.ws[i]
+            arr[i] = kfac_factor_item(desc, x.data_ptr(), out.data_ptr(), _ptr(ws),
+                                      0 if ws is None else ws.numel(), float(scale), int(op))
+        self.host = arr
+        self.dev = torch.frombuffer(bytearray(bytes(arr)), dtype=torch.uint8).to(device)
+
+
+def kfac_factor_batched(batch: FactorBatch, stream=None) -> None:
+    rc = load_library().kfac_factor_batched(batch.host, batch.dev.data_ptr(), batch.count, _stream(stream))
+    _check(rc, "kfac_factor_batched")
 
 
 def kfac_ema(running: torch.Tensor, fresh: torch.Tensor, dim: int, decay: float, stream=None) -> torch.Tensor:

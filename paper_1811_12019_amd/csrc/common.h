@@ -44,7 +44,7 @@ typedef short v8s __attribute__((ext_vector_type(8)));
 // Four floats that are only guaranteed dword alignment (rows of an odd-sized matrix).
 typedef v4f v4f_a4 __attribute__((aligned(4)));
 
-static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Pointers that kernels load from a descriptor table in memory have no known address space, and the compiler
@@ -87,7 +87,7 @@ struct Unfold {
     int d;               // columns incl. the bias column
 };
 
-static inline bool make_unfold_A(const kfac_layer_desc* L, Unfold* u) {
+static inline __host__ __device__ bool make_unfold_A(const kfac_layer_desc* L, Unfold* u) {
     if (!L) return false;
     if (L->N <= 0 || L->C_in <= 0 || L->H <= 0 || L->W <= 0 || L->C_out <= 0 || L->kh <= 0 || L->kw <= 0 ||
         L->stride <= 0 || L->pad < 0)
@@ -114,7 +114,7 @@ static inline bool make_unfold_A(const kfac_layer_desc* L, Unfold* u) {
     return true;
 }
 
-static inline bool make_unfold_G(const kfac_layer_desc* L, Unfold* u) {
+static inline __host__ __device__ bool make_unfold_G(const kfac_layer_desc* L, Unfold* u) {
     Unfold a;
     if (!make_unfold_A(L, &a)) return false;
     u->N = L->N; u->C = L->C_out; u->H = a.Ho; u->W = a.Wo;

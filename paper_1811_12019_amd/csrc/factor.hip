@@ -3,13 +3,17 @@
 // unfolded patch matrix is never materialised: tiles of it are gathered on the fly into LDS.
 //
 // Two kernels:
-//   factor_mfma_kernel     NHWC bf16/fp16, (kh, kw, c) column order, C % 8 == 0: matrix cores (factor_mfma.h).
+//   factor_dma_kernel      NHWC bf16/fp16, (kh, kw, c) column order, C % 8 == 0: matrix cores (factor_dma.h); many
+//                          builds can share one launch (workgroup -> (build, tile) through a prefix table).
 //   factor_generic_kernel  any layout / dtype / column order, fp32 FMA.  The fallback.
 // Both enumerate only the lower-triangular tiles of the symmetric output and mirror them, and both
 // can split the R unfolded rows over several workgroups (deterministic two-pass reduction through
 // the caller's workspace, no float atomics).
+#include <cstdlib>
+
 #include "common.h"
 #include "factor_mfma.h"
+#include "factor_dma.h"
 
 namespace kfac {
 
@@ -162,34 +166,33 @@ __global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const voi
 }
 
 // Second pass of a split build: sum the per-split partial tiles in a fixed order, scale, write the tile and its
-// mirror.  One workgroup per 32 x 32 sub-block of a tile (grid.y of them per tile): every thread owns four
-// consecutive columns of one row, so partial reads are 128-byte runs; the mirror goes through an LDS transpose.
+// mirror.  One workgroup per 32 x 32 sub-block of a tile: every thread owns four consecutive columns of one row, so
+// partial reads are 128-byte runs; the mirror goes through an LDS transpose.
 template <int T>
-__global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restrict__ partial, int nsplit, int d,
-                                                            float scale, float* __restrict__ out) {
-    __shared__ float tr[32][33];
+__device__ __forceinline__ void factor_reduce_block(const gfloat* __restrict__ partial, int nsplit, int ntiles,
+                                                    int tile, int sub, int d, float scale, gfloat* __restrict__ out,
+                                                    float (*tr)[33]) {
     int I, J;
-    tri_decode(blockIdx.x, I, J);
-    const int ntiles = gridDim.x;
+    tri_decode(tile, I, J);
     constexpr int SB = T / 32;
-    const int si = blockIdx.y / SB, sj = blockIdx.y - si * SB;
+    const int si = sub / SB, sj = sub - si * SB;
     const int lr = threadIdx.x >> 3, lc = (threadIdx.x & 7) * 4;
     const int trow = si * 32 + lr, tcol = sj * 32 + lc;              // inside the tile
     const int row = I * T + trow, col = J * T + tcol;
     if (I * T + si * 32 >= d || J * T + sj * 32 >= d) return;       // whole sub-block outside the matrix
     v4f s = {0.f, 0.f, 0.f, 0.f};
     if (row < d && col < d) {
-        const float* src = partial + (size_t)blockIdx.x * (T * T) + trow * T + tcol;
+        const gfloat* src = partial + (size_t)tile * (T * T) + trow * T + tcol;
         const size_t stride = (size_t)ntiles * (T * T);
         int sp = 0;
         for (; sp + 4 <= nsplit; sp += 4) {
-            v4f a = *(const v4f*)(src + (size_t)sp * stride);
-            v4f b = *(const v4f*)(src + (size_t)(sp + 1) * stride);
-            v4f c = *(const v4f*)(src + (size_t)(sp + 2) * stride);
-            v4f e = *(const v4f*)(src + (size_t)(sp + 3) * stride);
+            v4f a = *(const KFAC_AS1 v4f*)(src + (size_t)sp * stride);
+            v4f b = *(const KFAC_AS1 v4f*)(src + (size_t)(sp + 1) * stride);
+            v4f c = *(const KFAC_AS1 v4f*)(src + (size_t)(sp + 2) * stride);
+            v4f e = *(const KFAC_AS1 v4f*)(src + (size_t)(sp + 3) * stride);
             s += a; s += b; s += c; s += e;
         }
-        for (; sp < nsplit; ++sp) s += *(const v4f*)(src + (size_t)sp * stride);
+        for (; sp < nsplit; ++sp) s += *(const KFAC_AS1 v4f*)(src + (size_t)sp * stride);
         s *= scale;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
@@ -206,6 +209,13 @@ __global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restr
         for (int q = 0; q < 4; ++q)
             if (mcol + q < d) out[(size_t)mrow * d + mcol + q] = tr[lc + q][lr];
     }
+}
+
+template <int T>
+__global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restrict__ partial, int nsplit, int d,
+                                                            float scale, float* __restrict__ out) {
+    __shared__ float tr[32][33];
+    factor_reduce_block<T>(as_global(partial), nsplit, gridDim.x, blockIdx.x, blockIdx.y, d, scale, as_global(out), tr);
 }
 
 struct FactorPlan {
@@ -230,79 +240,179 @@ static FactorPlan plan_generic(const Unfold& u) {
     return p;
 }
 
-// The matrix-core kernel needs 16-byte channel vectors in (kh, kw, c) column order.
-static bool mfma_eligible(const Unfold& u) {
+// The matrix-core kernel needs 16-byte channel vectors in (kh, kw, c) column order, and its row decode is exact
+// below 2^24 rows.
+static __host__ __device__ bool dma_eligible(const Unfold& u) {
     if (u.dtype != KFAC_BF16 && u.dtype != KFAC_F16) return false;
     if (u.layout != KFAC_NHWC || (u.C & 7)) return false;
     if (u.order != KFAC_ORDER_KH_KW_C && !(u.kh == 1 && u.kw == 1)) return false;
-    return true;
+    return u.R < (1 << 24);
 }
 
-static FactorPlan plan_mfma(const Unfold& u) {
+static __host__ __device__ FactorPlan plan_dma(const Unfold& u) {
     FactorPlan p;
     p.tiles_dim = ceil_div(u.d, FT);
     p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
     int want = 512 / p.ntiles;             // about two workgroups per CU
-    int max_split = u.R / (8 * FK);        // at least eight K-stages per workgroup
+    int max_split = u.R / (8 * 64);        // at least 512 rows per workgroup
     int ns = want < max_split ? want : max_split;
     if (ns < 1) ns = 1;
     if (ns >= 8) ns = ns / 8 * 8;          // multiples of 8 keep a row range on one XCD
-    p.rows_per_split = ceil_div(ceil_div(u.R, ns), FK) * FK;
+    p.rows_per_split = ceil_div(ceil_div(u.R, ns), 64) * 64;
     p.nsplit = ceil_div(u.R, p.rows_per_split);
     p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * p.ntiles * FT * FT * sizeof(float) : 0;
     return p;
 }
 
+// ---- batched launches: many factor builds in one grid -------------------------------------------------------------
+constexpr int FMAXB = 120;
+
+struct FBatch {
+    const kfac_factor_item* table;   // device table, or nullptr -> `single`
+    kfac_factor_item single;
+    int count;
+    int index[FMAXB];                // table index of the i-th build of this launch
+    int prefix[FMAXB + 1];           // workgroup prefix sums
+};
+
+__device__ __forceinline__ int fbatch_locate(const FBatch& b, int wg, int& local) {
+    int lo = 0, hi = b.count;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (b.prefix[mid] <= wg) lo = mid; else hi = mid;
+    }
+    local = wg - b.prefix[lo];
+    return lo;
+}
+
 template <bool PLAIN, bool F16>
-static int launch_mfma(const Unfold& u, const FactorPlan& p, const void* x, float scale, float* out, float* ws,
-                       hipStream_t stream) {
+__global__ __launch_bounds__(256) void factor_dma_kernel(FBatch b) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    int local;
+    const int m = fbatch_locate(b, blockIdx.x, local);
+    const kfac_factor_item it = b.table ? b.table[b.index[m]] : b.single;
+    Unfold u;
+    if (it.op == KFAC_OP_FACTOR_A) make_unfold_A(&it.desc, &u); else make_unfold_G(&it.desc, &u);
+    const FactorPlan p = plan_dma(u);
+    const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
+    factor_dma_tile<PLAIN, F16>(u, (const KFAC_AS1 unsigned char*)it.x, scale, as_global(it.out),
+                                as_global((float*)it.ws), p.rows_per_split, p.ntiles, p.nsplit, local, smem);
+}
+
+__global__ __launch_bounds__(256) void factor_reduce_batched_kernel(FBatch b) {
+    __shared__ float tr[32][33];
+    int local;
+    const int m = fbatch_locate(b, blockIdx.x, local);
+    const kfac_factor_item it = b.table ? b.table[b.index[m]] : b.single;
+    Unfold u;
+    if (it.op == KFAC_OP_FACTOR_A) make_unfold_A(&it.desc, &u); else make_unfold_G(&it.desc, &u);
+    const FactorPlan p = plan_dma(u);
+    const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
+    constexpr int SUBS = (FT / 32) * (FT / 32);
+    factor_reduce_block<FT>(as_global((const float*)it.ws), p.nsplit, p.ntiles, local / SUBS, local % SUBS, u.d, scale,
+                            as_global(it.out), tr);
+}
+
+static bool item_unfold(const kfac_factor_item& it, Unfold* u) {
+    if (it.op == KFAC_OP_FACTOR_A) return make_unfold_A(&it.desc, u);
+    if (it.op == KFAC_OP_FACTOR_G) return make_unfold_G(&it.desc, u);
+    return false;
+}
+
+static size_t item_ws_bytes(const Unfold& u) {
+    size_t a = plan_generic(u).ws_bytes;                       // either kernel may serve the build
+    size_t b = dma_eligible(u) ? plan_dma(u).ws_bytes : 0;
+    return align_up(a > b ? a : b, 256);
+}
+
+static int check_item(const kfac_factor_item& it, Unfold* u) {
+    if (!item_unfold(it, u)) return KFAC_ERR_INVALID_ARG;
+    if (!it.x || !it.out) return KFAC_ERR_INVALID_ARG;
+    const size_t need = item_ws_bytes(*u);
+    if (need > 0 && (!it.ws || ((uintptr_t)it.ws & 255) || it.ws_bytes < need)) return KFAC_ERR_WORKSPACE;
+    return KFAC_OK;
+}
+
+template <bool PLAIN, bool F16>
+static int launch_dma_group(const FBatch& b, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)factor_mfma_kernel<PLAIN, F16>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, FACTOR_MFMA_LDS);
+        (void)hipFuncSetAttribute((const void*)factor_dma_kernel<PLAIN, F16>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, FACTOR_DMA_LDS);
         attr_set = true;
     }
     void* tok = nullptr;
-    if (timing_enabled()) timing_begin("factor_mfma_kernel", stream, &tok);
-    hipLaunchKernelGGL((factor_mfma_kernel<PLAIN, F16>), dim3(p.ntiles * p.nsplit), dim3(256), FACTOR_MFMA_LDS, stream,
-                       u, (const uint16_t*)x, scale, out, ws, p.rows_per_split, p.ntiles, p.nsplit);
+    if (timing_enabled()) timing_begin(PLAIN ? "factor_dma_kernel<plain>" : "factor_dma_kernel<conv>", stream, &tok);
+    hipLaunchKernelGGL((factor_dma_kernel<PLAIN, F16>), dim3(b.prefix[b.count]), dim3(256), FACTOR_DMA_LDS, stream, b);
     if (tok) timing_end(stream, tok);
     if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
     return KFAC_OK;
 }
 
-static int run_factor(const Unfold& u, const void* x, float scale, float* out, void* ws, size_t ws_bytes,
-                      hipStream_t stream) {
-    if (!x || !out) return KFAC_ERR_INVALID_ARG;
-    if (scale == 0.f) scale = 1.0f / (float)u.R;
-    if (mfma_eligible(u) && ((uintptr_t)x & 15) == 0) {
-        FactorPlan p = plan_mfma(u);
-        if (p.ws_bytes > 0) {
-            if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
-        }
-        const bool plain = u.kh == 1 && u.kw == 1 && u.stride == 1 && u.pad == 0;
-        const bool f16 = u.dtype == KFAC_F16;
-        int rc = plain ? (f16 ? launch_mfma<true, true>(u, p, x, scale, out, (float*)ws, stream)
-                              : launch_mfma<true, false>(u, p, x, scale, out, (float*)ws, stream))
-                       : (f16 ? launch_mfma<false, true>(u, p, x, scale, out, (float*)ws, stream)
-                              : launch_mfma<false, false>(u, p, x, scale, out, (float*)ws, stream));
-        if (rc != KFAC_OK) return rc;
-        if (p.nsplit > 1) {
-            KFAC_LAUNCH(factor_reduce_kernel<FT>, dim3(p.ntiles, (FT / 32) * (FT / 32)), dim3(256), stream, (const float*)ws, p.nsplit,
-                        u.d, scale, out);
-        }
-        return KFAC_OK;
-    }
+static int run_generic(const Unfold& u, const kfac_factor_item& it, hipStream_t stream) {
+    const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     FactorPlan p = plan_generic(u);
-    if (p.ws_bytes > 0) {
-        if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes) return KFAC_ERR_WORKSPACE;
-    }
     dim3 grid(p.ntiles, p.nsplit);
-    KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, x, scale, out, (float*)ws,
-                       p.rows_per_split);
+    KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, it.x, scale, it.out, (float*)it.ws, p.rows_per_split);
     if (p.nsplit > 1) {
-        KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, (GT / 32) * (GT / 32)), dim3(256), stream, (const float*)ws,
-                           p.nsplit, u.d, scale, out);
+        KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, (GT / 32) * (GT / 32)), dim3(256), stream,
+                    (const float*)it.ws, p.nsplit, u.d, scale, it.out);
+    }
+    return KFAC_OK;
+}
+
+// All builds of items[0..count): matrix-core builds grouped by kernel variant into batched launches, the rest one
+// by one through the generic kernel.  `dev` may be nullptr only when count == 1.
+static int run_factor_items(const kfac_factor_item* host, const kfac_factor_item* dev, int count, hipStream_t stream) {
+    for (int i = 0; i < count; ++i) {
+        Unfold u;
+        int rc = check_item(host[i], &u);
+        if (rc != KFAC_OK) return rc;
+    }
+    // variants: 0 plain bf16, 1 plain f16, 2 conv bf16, 3 conv f16
+    for (int variant = 0; variant < 4; ++variant) {
+        int next = 0;
+        while (next < count) {
+            FBatch b, r;
+            b.table = r.table = dev;
+            b.count = r.count = 0;
+            b.prefix[0] = r.prefix[0] = 0;
+            for (; next < count && b.count < FMAXB; ++next) {
+                Unfold u;
+                item_unfold(host[next], &u);
+                if (!dma_eligible(u) || ((uintptr_t)host[next].x & 15)) continue;
+                const bool plain = u.kh == 1 && u.kw == 1 && u.stride == 1 && u.pad == 0;
+                const bool f16 = u.dtype == KFAC_F16;
+                if ((plain ? 0 : 2) + (f16 ? 1 : 0) != variant) continue;
+                const FactorPlan p = plan_dma(u);
+                b.index[b.count] = next;
+                b.prefix[b.count + 1] = b.prefix[b.count] + p.ntiles * p.nsplit;
+                if (!dev) b.single = host[next];
+                ++b.count;
+                if (p.nsplit > 1) {
+                    r.index[r.count] = next;
+                    r.prefix[r.count + 1] = r.prefix[r.count] + p.ntiles * (FT / 32) * (FT / 32);
+                    if (!dev) r.single = host[next];
+                    ++r.count;
+                }
+            }
+            if (b.count == 0) continue;
+            int rc = variant == 0 ? launch_dma_group<true, false>(b, stream)
+                   : variant == 1 ? launch_dma_group<true, true>(b, stream)
+                   : variant == 2 ? launch_dma_group<false, false>(b, stream)
+                                  : launch_dma_group<false, true>(b, stream);
+            if (rc != KFAC_OK) return rc;
+            if (r.count > 0) {
+                KFAC_LAUNCH(factor_reduce_batched_kernel, dim3(r.prefix[r.count]), dim3(256), stream, r);
+            }
+        }
+    }
+    for (int i = 0; i < count; ++i) {
+        Unfold u;
+        item_unfold(host[i], &u);
+        if (dma_eligible(u) && ((uintptr_t)host[i].x & 15) == 0) continue;
+        int rc = run_generic(u, host[i], stream);
+        if (rc != KFAC_OK) return rc;
     }
     return KFAC_OK;
 }
@@ -315,21 +425,29 @@ extern "C" size_t kfac_factor_workspace_bytes(int op, const kfac_layer_desc* des
     Unfold u;
     bool ok = op == KFAC_OP_FACTOR_A ? make_unfold_A(desc, &u) : op == KFAC_OP_FACTOR_G ? make_unfold_G(desc, &u) : false;
     if (!ok) return 0;
-    size_t a = plan_generic(u).ws_bytes;                       // either kernel may serve the call
-    size_t b = mfma_eligible(u) ? plan_mfma(u).ws_bytes : 0;
-    return align_up(a > b ? a : b, 256);
+    return item_ws_bytes(u);
+}
+
+static int factor_single(int op, const kfac_layer_desc* desc, const void* x, float scale, float* out, void* ws,
+                         size_t ws_bytes, void* stream) {
+    if (!desc) return KFAC_ERR_INVALID_ARG;
+    kfac_factor_item it;
+    it.desc = *desc; it.x = x; it.out = out; it.ws = ws; it.ws_bytes = ws_bytes; it.scale = scale; it.op = op;
+    return run_factor_items(&it, nullptr, 1, (hipStream_t)stream);
 }
 
 extern "C" int kfac_factor_A(const kfac_layer_desc* desc, const void* act, float scale, float* A, void* ws,
                              size_t ws_bytes, void* stream) {
-    Unfold u;
-    if (!make_unfold_A(desc, &u)) return KFAC_ERR_INVALID_ARG;
-    return run_factor(u, act, scale, A, ws, ws_bytes, (hipStream_t)stream);
+    return factor_single(KFAC_OP_FACTOR_A, desc, act, scale, A, ws, ws_bytes, stream);
 }
 
 extern "C" int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, float scale, float* G, void* ws,
                              size_t ws_bytes, void* stream) {
-    Unfold u;
-    if (!make_unfold_G(desc, &u)) return KFAC_ERR_INVALID_ARG;
-    return run_factor(u, gout, scale, G, ws, ws_bytes, (hipStream_t)stream);
+    return factor_single(KFAC_OP_FACTOR_G, desc, gout, scale, G, ws, ws_bytes, stream);
+}
+
+extern "C" int kfac_factor_batched(const kfac_factor_item* items_host, const kfac_factor_item* items_dev, int32_t count,
+                                   void* stream) {
+    if (!items_host || !items_dev || count <= 0) return KFAC_ERR_INVALID_ARG;
+    return run_factor_items(items_host, items_dev, count, (hipStream_t)stream);
 }

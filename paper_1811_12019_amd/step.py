@@ -54,9 +54,11 @@ class KfacNetworkStep:
         self.decay = decay
         self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
         self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
-        ws_f = max(max(kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_A, l.desc),
-                       kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_G, l.desc)) for l in self.layers)
-        self.ws_factor = kb.alloc_workspace(ws_f, device)
+        builds = []
+        for l in self.layers:
+            builds.append((kb.KFAC_OP_FACTOR_A, l.desc, l.act, l.A_new, 0.0))
+            builds.append((kb.KFAC_OP_FACTOR_G, l.desc, l.gout, l.G_new, 0.0))
+        self.factor_batch = kb.FactorBatch(builds, device=device)
         self.pre_batch = kb.PrecondBatch([l.G_inv for l in self.layers], [l.A_inv for l in self.layers],
                                          [l.gradW for l in self.layers], [l.P for l in self.layers], device=device)
         src = []
@@ -69,9 +71,7 @@ class KfacNetworkStep:
 
     # -- stages ------------------------------------------------------------------------------
     def build_factors(self, stream=None):
-        for l in self.layers:
-            kb.kfac_factor_A(l.desc, l.act, 0.0, l.A_new, self.ws_factor, stream)
-            kb.kfac_factor_G(l.desc, l.gout, 0.0, l.G_new, self.ws_factor, stream)
+        kb.kfac_factor_batched(self.factor_batch, stream)
 
     def update_running(self, stream=None):
         if self.decay is None:

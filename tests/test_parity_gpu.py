@@ -106,6 +106,33 @@ def test_factors_resnet_layers_full_size(name):
     check_factor_pair(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C, seed=5)
 
 
+def test_factor_batched_matches_single_calls():
+    """A mixed batch (1x1, 3x3, strided, fc, a layer only the generic kernel serves) equals the single calls bit for bit."""
+    shapes = [SMALL_SHAPES[0], SMALL_SHAPES[1], SMALL_SHAPES[3], SMALL_SHAPES[4], SMALL_SHAPES[5], SMALL_SHAPES[2]]
+    builds, keep, singles = [], [], []
+    for i, shp in enumerate(shapes):
+        desc = kb.make_desc(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+        act = synth.round_to_bf16(synth.make_act(shp, 7 + i))
+        gout = synth.round_to_bf16(synth.make_gout(shp, 7 + i))
+        at = kb.to_device_tensor(act, kb.KFAC_NHWC, kb.KFAC_BF16, DEV)
+        gt = kb.to_device_tensor(gout, kb.KFAC_NHWC, kb.KFAC_BF16, DEV)
+        A = torch.full((shp.d_A, shp.d_A), float("nan"), device=DEV)
+        G = torch.full((shp.d_G, shp.d_G), float("nan"), device=DEV)
+        builds += [(kb.KFAC_OP_FACTOR_A, desc, at, A, 0.0), (kb.KFAC_OP_FACTOR_G, desc, gt, G, 0.0)]
+        keep.append((shp, act, gout, A, G))
+    batch = kb.FactorBatch(builds, device=DEV)
+    kb.kfac_factor_batched(batch)
+    torch.cuda.synchronize()
+    for shp, act, gout, A, G in keep:
+        A_ref = ko.factor_A(act, shp.kh, shp.kw, shp.stride, shp.pad, True, ko.ORDER_KH_KW_C)
+        assert rel_fro(A.cpu().numpy(), A_ref) < FACTOR_TOL
+        assert rel_fro(G.cpu().numpy(), ko.factor_G(gout)) < FACTOR_TOL
+        np.testing.assert_array_equal(A.cpu().numpy(), gpu_factor(kb.KFAC_OP_FACTOR_A, shp, act, kb.KFAC_NHWC,
+                                                                  kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C))
+        np.testing.assert_array_equal(G.cpu().numpy(), gpu_factor(kb.KFAC_OP_FACTOR_G, shp, gout, kb.KFAC_NHWC,
+                                                                  kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C))
+
+
 def test_factor_scale_argument():
     shp = SMALL_SHAPES[0]
     act = synth.round_to_bf16(synth.make_act(shp, 2))

@@ -138,13 +138,16 @@ def main():
 
     stages = stage_times(net)
     # per-kernel durations over `steps` more steps, HIP events around every launch on the launch stream
+    # (the inversion groups run back to back here: kernels that share the GPU would stretch each other's events)
+    net.overlap_inversions = False
     kb.kfac_kernel_timing_enable(True)
     for _ in range(args.steps):
         net.step()
     torch.cuda.synchronize()
     report = kb.kfac_kernel_timing_report()
     kb.kfac_kernel_timing_enable(False)
-    infos = torch.stack([net.inv_batch.info]).cpu()
+    net.overlap_inversions = True
+    infos = net.inverse_info().cpu()
     assert int(infos.abs().max()) == 0, "an inversion reported a non-positive-definite factor"
 
     work = kernel_work(net)

@@ -113,10 +113,10 @@ size_t kfac_inverse_workspace_bytes(int32_t dim);
 int kfac_damped_inverse(const float* S, int32_t dim, float damping, float* Minv, int32_t* info,
                         void* ws, size_t ws_bytes, void* stream);
 
-/* A batch of independent inversions advanced together (one launch per elimination step for the whole
- * batch), for the many factors of a network.  items_host[i] and items_dev[i] describe the same matrix;
- * items_dev is the device-resident copy the kernels read (the caller uploads it once, outside the step).
- * Each item's `ws` needs kfac_inverse_workspace_bytes(dim) bytes of its own. */
+/* A batch of independent inversions advanced together (one launch per elimination stage per step for the whole
+ * batch), for the many factors of a network.  items_host is a HOST array, sorted by non-increasing dim; the
+ * descriptors travel in the kernel arguments, so nothing has to be uploaded.  Each item's `ws` needs
+ * kfac_inverse_workspace_bytes(dim) bytes of its own.  Results are identical to the single calls. */
 typedef struct kfac_inverse_item {
     const float* S;     /* dim x dim symmetric input (device)                                             */
     float* Minv;        /* dim x dim output (device)                                                      */
@@ -126,8 +126,7 @@ typedef struct kfac_inverse_item {
     float damping;
 } kfac_inverse_item;
 
-int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, const kfac_inverse_item* items_dev,
-                                int32_t count, void* stream);
+int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, int32_t count, void* stream);
 
 /* Workspace for kfac_precondition (the d_A x d_G intermediate). */
 size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA);

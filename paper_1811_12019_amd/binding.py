@@ -93,7 +93,7 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_damped_inverse.restype = ctypes.c_int
     lib.kfac_damped_inverse.argtypes = [vp, i32, f32, vp, vp, vp, sz, vp]
     lib.kfac_damped_inverse_batched.restype = ctypes.c_int
-    lib.kfac_damped_inverse_batched.argtypes = [itemp, vp, i32, vp]
+    lib.kfac_damped_inverse_batched.argtypes = [itemp, i32, vp]
     lib.kfac_precondition_workspace_bytes.restype = sz
     lib.kfac_precondition_workspace_bytes.argtypes = [i32, i32]
     lib.kfac_precondition.restype = ctypes.c_int
@@ -219,7 +219,7 @@ def kfac_damped_inverse(S: torch.Tensor, dim: int, damping: float, Minv: torch.T
 
 
 class InverseBatch:
-    """Host + device copies of a kfac_inverse_item table (built once, reused every step)."""
+    """A kfac_inverse_item table (host memory; built once, reused every step) and the scratch it points to."""
 
     def __init__(self, S: Sequence[torch.Tensor], Minv: Sequence[torch.Tensor], dampings: Sequence[float],
                  info: Optional[torch.Tensor] = None, device="cuda"):
@@ -235,12 +235,10 @@ class InverseBatch:
             arr[slot] = kfac_inverse_item(S[i].data_ptr(), Minv[i].data_ptr(), _ptr(self.ws[i]),
                                           self.info.data_ptr() + 4 * i, dims[i], float(dampings[i]))
         self.host = arr
-        raw = bytes(arr)
-        self.dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
 
 
 def kfac_damped_inverse_batched(batch: InverseBatch, stream=None) -> None:
-    rc = load_library().kfac_damped_inverse_batched(batch.host, batch.dev.data_ptr(), batch.count, _stream(stream))
+    rc = load_library().kfac_damped_inverse_batched(batch.host, batch.count, _stream(stream))
     _check(rc, "kfac_damped_inverse_batched")
 
 

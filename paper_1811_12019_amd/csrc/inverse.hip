@@ -22,7 +22,7 @@
 namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
-constexpr int MAXB = 120;        // matrices per launch group
+constexpr int MAXB = 64;         // matrices per launch group (bounded by the 4 KB of kernel arguments)
 #ifndef UPD_TK
 #define UPD_TK 16
 #endif
@@ -39,12 +39,17 @@ __device__ unsigned long long g_trace[4096 * 16];
 #define TR(slot) do { } while (0)
 #endif
 
+// Everything a launch needs to know about its matrices travels in the kernel arguments (scalar loads, no dependent
+// memory round trip at the start of every workgroup).
 struct Batch {
-    const kfac_inverse_item* table;   // device table, or nullptr -> `single`
-    kfac_inverse_item single;
-    int first;                        // index of the first matrix of this group in `table`
-    int count;                        // active matrices in this launch
-    int prefix[MAXB + 1];             // workgroup prefix sums over the active matrices
+    int count;                        // matrices in this launch
+    int prefix[MAXB + 1];             // workgroup prefix sums over them
+    int dim[MAXB];
+    float damping[MAXB];
+    const float* S[MAXB];
+    float* Minv[MAXB];
+    void* ws[MAXB];
+    int32_t* info[MAXB];
 };
 
 // One matrix of the batch as the kernels see it: pointers typed as global memory.
@@ -58,14 +63,13 @@ struct Item {
 };
 
 __device__ __forceinline__ Item get_item(const Batch& b, int m) {
-    const kfac_inverse_item raw = b.table ? b.table[b.first + m] : b.single;
     Item it;
-    it.S = as_global(raw.S);
-    it.Minv = as_global(raw.Minv);
-    it.ws = as_global((float*)raw.ws);
-    it.info = as_global((int*)raw.info);
-    it.dim = raw.dim;
-    it.damping = raw.damping;
+    it.S = as_global(b.S[m]);
+    it.Minv = as_global(b.Minv[m]);
+    it.ws = as_global((float*)b.ws[m]);
+    it.info = as_global((int*)b.info[m]);
+    it.dim = b.dim[m];
+    it.damping = b.damping[m];
     return it;
 }
 
@@ -412,8 +416,15 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                if (row < rows && col < nb) ws.T[(size_t)(r0 + row) * NB + col] = acc.c[mb][nbk][r];
+                if (row < rows) ws.T[(size_t)(r0 + row) * NB + col] = col < nb ? acc.c[mb][nbk][r] : 0.f;
             }
+    // the update streams whole 16-float slabs of T and U: keep the columns beyond a ragged block at zero
+    if (nb < NB) {
+        for (int e = threadIdx.x; e < rows * NB; e += 256) {
+            const int row = e >> 7, col = e & (NB - 1);
+            if (col >= nb) ws.U[(size_t)(r0 + row) * NB + col] = 0.f;
+        }
+    }
 }
 
 // One tile (I >= J) of one elimination step.  Tile kinds:
@@ -479,33 +490,126 @@ __device__ __forceinline__ void upd_flush(const UpdCtx& c, float* __restrict__ s
     }
 }
 
+// Regular tile: acc = T_I . U_J^T with both operand panels (128 rows x nb floats, row stride 128, zero beyond nb)
+// streamed through a 3-stage LDS ring by global_load_lds_dwordx4 (lane i's 16 bytes land at block base + 16 i), so
+// no registers are spent on staging and one barrier per 16-wide K-slab suffices.  Inside a 1 KB block (16 rows x 4
+// chunks of 4 floats) chunk c of row r sits in slot 4 r + (c ^ ((r >> 1) & 3)): the MFMA operand reads (one float4
+// per lane, 32 consecutive rows per half-wave) are then bank-conflict free.
+constexpr int UK = 16;                    // K-slab
+constexpr int UNS = 3;                    // ring stages
+constexpr int UPANEL = 8 * 1024;          // bytes per operand panel per stage
+constexpr int USTAGE = 2 * UPANEL;
+static_assert(UNS * USTAGE <= GEMM_LDS_FLOATS * 4 + 12288, "ring must fit the kernel's LDS");
+
+#define KFAC_LDS_READ128(dst, addr, off) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
+
 template <bool LAST>
 __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __restrict__ U, float* __restrict__ lds) {
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
     const int pr = t >> 5, pc = (t & 31) * 4;
     constexpr int sld = LAST ? SLD_T : SLD;
-    TileAcc acc;
-    TR(1);
-    tile_mma_nt<false, UPD_TK>(c.T + (size_t)c.i0 * NB, NB, c.irows, U + (size_t)c.j0 * NB, NB, c.jrows, c.nb, lds, acc,
-                           nullptr, 0, c.diag);
     const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
-    TR(2);
-#pragma unroll 1
-    for (int half = 0; half < 2; ++half) {
-        const int h0 = half * 64;
-        if (h0 >= c.irows) break;                          // uniform
-        if (half == 1) __syncthreads();                    // everyone is done with the first half's stage
-        TR(3 + 3 * half);
-        // old values of this half, all fetched before anything is stored (loads and stores go to the same array:
-        // interleaving them would serialise the memory round trips)
-        v4f oldv[8];
+    lds_byte* l0 = (lds_byte*)lds;
+
+    // LAST: old values are fetched row-wise (the epilogue transposes through LDS for the mirror image).
+    v4f oldv[8];
+    if constexpr (LAST) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
-            const int row = h0 + pr + 8 * p;
+            const int row = pr + 8 * p;
             v4f o = {0.f, 0.f, 0.f, 0.f};
             if (row < c.irows && c.j0 + pc < c.ldw) o = *(const KFAC_AS1 v4f*)&c.W[(size_t)(c.i0 + row) * c.ldw + c.j0 + pc];
             oldv[p] = o;
         }
+    }
+
+    // ---- producer: wavefronts 0,1 stream T_I, wavefronts 2,3 stream U_J; four 1 KB blocks each per stage ----
+    const int pan = wave >> 1;
+    const int drow = lane >> 2, dchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const gfloat* src0 = (pan == 0 ? c.T + (size_t)c.i0 * NB : U + (size_t)c.j0 * NB) + (size_t)drow * NB + 4 * dchunk;
+    const int nst = (c.nb + UK - 1) / UK;
+    auto issue = [&](int s, int buf) {
+        const int sc = s < nst ? s : nst - 1;              // past the end: re-read the last slab (never consumed)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int b = (wave & 1) + 2 * j;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src0 + (size_t)(16 * b) * NB + sc * UK),
+                                             (__attribute__((address_space(3))) void*)(l0 + buf * USTAGE + pan * UPANEL + b * 1024),
+                                             16, 0, 0);
+        }
+    };
+
+    // ---- consumer: per-lane LDS byte addresses of the float4 holding k = 8 s2 + 4 h .. +3 of its row ----
+    unsigned a_addr[2][2], b_addr[2][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int ma = wm * 64 + q * 32 + lm, mb_ = wn * 64 + q * 32 + lm;
+            const int ch = 2 * s2 + h;
+            a_addr[q][s2] = (unsigned)((ma >> 4) * 1024 + (4 * (ma & 15) + (ch ^ (((ma & 15) >> 1) & 3))) * 16);
+            b_addr[q][s2] = (unsigned)(UPANEL + (mb_ >> 4) * 1024 + (4 * (mb_ & 15) + (ch ^ (((mb_ & 15) >> 1) & 3))) * 16);
+        }
+
+    TileAcc acc;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = 0.f;
+
+    TR(1);
+    issue(0, 0);
+    issue(1, 1);
+    for (int it = 0; it < nst; it += UNS) {
+#pragma unroll
+        for (int bi = 0; bi < UNS; ++bi) {
+            const int s = it + bi;
+            if (s >= nst) break;                                            // uniform
+            asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");   // slab s landed (everybody's part)
+            issue(s + 2, (bi + 2) % UNS);                                    // refill the slot slab s-1 vacated
+            if (!dead) {
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    v4f a[2], bb[2];
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        KFAC_LDS_READ128(a[q], a_addr[q][s2], bi * USTAGE);
+                        KFAC_LDS_READ128(bb[q], b_addr[q][s2], bi * USTAGE);
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(bb[0]), "+v"(bb[1]));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                            for (int nbk = 0; nbk < 2; ++nbk)
+                                acc.c[mb][nbk] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb][i], bb[nbk][i], acc.c[mb][nbk], 0, 0, 0);
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");            // ring idle: LDS becomes the epilogue stage
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int h0 = half * 64;
+        if (h0 >= c.irows) break;                          // uniform
+        if (half == 1) {
+            __syncthreads();                               // everyone is done with the first half's stage
+            // old values of the second half, all fetched before anything more is stored
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = h0 + pr + 8 * p;
+                v4f o = {0.f, 0.f, 0.f, 0.f};
+                if (row < c.irows && c.j0 + pc < c.ldw) o = *(const KFAC_AS1 v4f*)&c.W[(size_t)(c.i0 + row) * c.ldw + c.j0 + pc];
+                oldv[p] = o;
+            }
+        }
+        TR(3 + 3 * half);
         if (wm == half) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -522,6 +626,161 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
         upd_flush<LAST, true>(c, lds, h0, oldv);
         TR(5 + 3 * half);
     }
+}
+
+// Regular tile of a step that is not the matrix's last one: new = old - T_I U_J^T goes back into the working copy.
+// Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot block is
+// full: exactly 8 K-slabs, unrolled.  The product accumulates (negated) from zero; the tile's old values are fetched
+// straight into MFMA register layout (register r of a 32 x 32 block: 32 consecutive floats of one row per half-wave)
+// in two halves of 32 registers while the slabs are multiplied, added to the accumulators once they have landed, and
+// the result is stored from the registers: HBM reads overlap the product and nothing is staged in LDS.
+// Vector-memory operations complete in issue order, so "slab s landed" is a count of the operations issued after
+// that slab's four loads; every lane issues every load (addresses are clamped into the workspace, never skipped)
+// to keep that count the same for all wavefronts.
+#define KFAC_VM_WAIT_BARRIER(n) asm volatile("s_waitcnt vmcnt(" #n ")\n\ts_barrier" ::: "memory")
+
+__device__ __forceinline__ void upd_regular_mid(const UpdCtx& c, const gfloat* __restrict__ U, float* __restrict__ lds) {
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
+    lds_byte* l0 = (lds_byte*)lds;
+
+    // ---- producer: wavefronts 0,1 stream T_I, wavefronts 2,3 stream U_J; four 1 KB blocks each per stage ----
+    const int pan = wave >> 1;
+    const int drow = lane >> 2, dchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const gfloat* src0 = (pan == 0 ? c.T + (size_t)c.i0 * NB : U + (size_t)c.j0 * NB) + (size_t)drow * NB + 4 * dchunk;
+    auto issue = [&](int s, int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int b = (wave & 1) + 2 * j;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src0 + (size_t)(16 * b) * NB + s * UK),
+                                             (__attribute__((address_space(3))) void*)(l0 + buf * USTAGE + pan * UPANEL + b * 1024),
+                                             16, 0, 0);
+        }
+    };
+
+    // ---- consumer: per-lane LDS byte addresses of the float4 holding k = 8 s2 + 4 h .. +3 of its row ----
+    unsigned a_addr[2][2], b_addr[2][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int ma = wm * 64 + q * 32 + lm, mb_ = wn * 64 + q * 32 + lm;
+            const int ch = 2 * s2 + h;
+            a_addr[q][s2] = (unsigned)((ma >> 4) * 1024 + (4 * (ma & 15) + (ch ^ (((ma & 15) >> 1) & 3))) * 16);
+            b_addr[q][s2] = (unsigned)(UPANEL + (mb_ >> 4) * 1024 + (4 * (mb_ & 15) + (ch ^ (((mb_ & 15) >> 1) & 3))) * 16);
+        }
+
+    // ---- the tile in the working copy: uniform base + per-lane byte offset (one per 32-column block) ----
+    // Rows up to the padded dimension exist in the workspace, so only columns need clamping for the loads.
+    gfloat* wtile = c.W + (size_t)c.i0 * c.ldw + c.j0;
+    const unsigned long long wt = (unsigned long long)wtile;                       // uniform: keep it in scalar registers
+    // (readfirstlane returns int: go through unsigned, or a low word with bit 31 set would sign-extend into the high word)
+    const unsigned wt_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)wt);
+    const unsigned wt_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(wt >> 32));
+    const unsigned long long wts = ((unsigned long long)wt_hi << 32) | (unsigned long long)wt_lo;
+    const unsigned row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(c.ldw) * 4u;
+    bool colok[2];
+    unsigned voff[2];
+#pragma unroll
+    for (int nbk = 0; nbk < 2; ++nbk) {
+        colok[nbk] = c.j0 + wn * 64 + nbk * 32 < c.ldw;
+        const int col = colok[nbk] ? wn * 64 + nbk * 32 + lm : lm;
+        voff[nbk] = (unsigned)(((wm * 64 + 4 * h) * c.ldw + col) * 4);
+    }
+    const int rows_left = c.irows - wm * 64 - 4 * h;      // tile rows from the lane's first row on
+
+    float old[2][16];
+    auto load_old = [&](int mb, int nbk) {                // 16 loads
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const unsigned long long base = wts + (unsigned long long)(mb * 32 + (r >> 2) * 8 + (r & 3)) * row_bytes;
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(old[nbk][r]) : "v"(voff[nbk]), "s"(base) : "memory");
+        }
+    };
+    auto landed = [&]() {                                 // orders every later use of old[][] after the wait before it
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+            asm volatile("" : "+v"(old[nbk][0]), "+v"(old[nbk][1]), "+v"(old[nbk][2]), "+v"(old[nbk][3]), "+v"(old[nbk][4]),
+                         "+v"(old[nbk][5]), "+v"(old[nbk][6]), "+v"(old[nbk][7]), "+v"(old[nbk][8]), "+v"(old[nbk][9]),
+                         "+v"(old[nbk][10]), "+v"(old[nbk][11]), "+v"(old[nbk][12]), "+v"(old[nbk][13]), "+v"(old[nbk][14]),
+                         "+v"(old[nbk][15]));
+    };
+
+    TileAcc acc;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = 0.f;
+
+    TR(1);
+    issue(0, 0);
+    issue(1, 1);
+    // Issue order per slab s: [slab s+2's four loads] [16 old-value loads in slabs 0, 1, 4, 5].
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        // operations that may still be in flight once slab s has landed
+        if (s == 0) KFAC_VM_WAIT_BARRIER(4);              // slab 1
+        else if (s == 1) KFAC_VM_WAIT_BARRIER(20);        // slab 2, old (0,0)
+        else if (s == 2) KFAC_VM_WAIT_BARRIER(36);        // old (0,0), slab 3, old (0,1)
+        else if (s == 3) KFAC_VM_WAIT_BARRIER(20);        // old (0,1), slab 4
+        else if (s == 4) KFAC_VM_WAIT_BARRIER(4);         // slab 5: the first half of the old values is in
+        else if (s == 5) KFAC_VM_WAIT_BARRIER(20);        // slab 6, old (1,0)
+        else if (s == 6) KFAC_VM_WAIT_BARRIER(36);        // old (1,0), slab 7, old (1,1)
+        else KFAC_VM_WAIT_BARRIER(16);                    // old (1,1)
+        if (s == 0) TR(2);
+        if (s + 2 < 8) issue(s + 2, (s + 2) % UNS);       // refill the slot slab s-1 vacated
+        if (s == 4) {
+            landed();
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc.c[0][nbk][r] += old[nbk][r];
+        }
+        if (s == 0 || s == 1) load_old(0, s);
+        if (s == 4 || s == 5) load_old(1, s - 4);
+        if (!dead) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                v4f a[2], bb[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    KFAC_LDS_READ128(a[q], a_addr[q][s2], (s % UNS) * USTAGE);
+                    KFAC_LDS_READ128(bb[q], b_addr[q][s2], (s % UNS) * USTAGE);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(bb[0]), "+v"(bb[1]));
+                a[0] = -a[0]; a[1] = -a[1];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int nbk = 0; nbk < 2; ++nbk)
+                            acc.c[mb][nbk] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb][i], bb[nbk][i], acc.c[mb][nbk], 0, 0, 0);
+            }
+        }
+    }
+    TR(3);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    landed();
+    TR(4);
+    if (dead) return;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                const float v = acc.c[mb][nbk][r] + (mb == 1 ? old[nbk][r] : 0.f);
+                if (colok[nbk] && dr < rows_left)
+                    *(gfloat*)((KFAC_AS1 char*)(wtile + (size_t)dr * c.ldw) + voff[nbk]) = v;
+            }
+    TR(5);
 }
 
 // column tile (from_rows = true): new[a][c] = T[(i0 + a)][c];  row tile: new[a][c] = T[(j0 + c)][a]
@@ -563,7 +822,7 @@ __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* _
 
 template <bool LAST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b, int step) {
-    __shared__ float lds[GEMM_LDS_FLOATS];
+    __shared__ __attribute__((aligned(1024))) float lds[UNS * USTAGE / 4];
     TR(0);
     int m, tile;
     locate(b, blockIdx.x, m, tile);
@@ -580,47 +839,52 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
     c.nb = min(NB, c.d - step * NB);
     c.diag = I == J;
-    if (I != kb && J != kb) upd_regular<LAST>(c, ws.U, lds);
+    if (I != kb && J != kb) {
+        if constexpr (LAST) upd_regular<true>(c, ws.U, lds);
+        else upd_regular_mid(c, ws.U, lds);
+    }
     else upd_panel<LAST>(c, J == kb, lds);
 }
 
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
 
+static void fill_batch(Batch& b, const kfac_inverse_item* items, int count) {
+    b.count = count;
+    for (int i = 0; i < count; ++i) {
+        b.dim[i] = items[i].dim;
+        b.damping[i] = items[i].damping;
+        b.S[i] = items[i].S;
+        b.Minv[i] = items[i].Minv;
+        b.ws[i] = items[i].ws;
+        b.info[i] = items[i].info;
+    }
+}
+
 // items must be sorted by non-increasing dim (checked by the caller of this function).
-static int run_group(const kfac_inverse_item* host, const kfac_inverse_item* dev, int first, int count,
-                     hipStream_t stream) {
+static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) {
     Batch b;
-    b.table = dev;
-    b.first = first;
-    if (!dev) b.single = host[first];
-    const kfac_inverse_item* h = host + first;
     const int max_steps = nblk_of(h[0].dim);
 
     // matrices needing the blocked path (more than one block) come first in the sorted order
     int n_multi = 0;
     while (n_multi < count && nblk_of(h[n_multi].dim) > 1) ++n_multi;
 
-    if (n_multi > 0) {
-        b.count = n_multi;
-        b.prefix[0] = 0;
-        for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-        KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
-    }
     if (count > n_multi) {
         // single-block matrices: damp, invert and write in one kernel, straight from S
-        Batch s = b;
-        s.first = first + n_multi;
-        if (!dev) s.single = host[first + n_multi];
-        s.count = count - n_multi;
-        KFAC_LAUNCH(inv_pivot_kernel, dim3(s.count), dim3(256), stream, s, 0, 1);
+        fill_batch(b, h + n_multi, count - n_multi);
+        KFAC_LAUNCH(inv_pivot_kernel, dim3(b.count), dim3(256), stream, b, 0, 1);
     }
+    if (n_multi == 0) return KFAC_OK;
+    fill_batch(b, h, n_multi);
+    b.prefix[0] = 0;
+    for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
+    KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
     for (int step = 0; step < max_steps; ++step) {
         int active = 0;   // multi-block matrices that still have a block `step`
         while (active < n_multi && nblk_of(h[active].dim) > step) ++active;
         if (active == 0) break;
         b.count = active;
         KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);
-        b.prefix[0] = 0;
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
         KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
         // matrices in their final step (they sit at the end of the active range) write the caller's output
@@ -632,11 +896,10 @@ static int run_group(const kfac_inverse_item* host, const kfac_inverse_item* dev
             KFAC_LAUNCH(inv_update_kernel<false>, dim3(b.prefix[b.count]), dim3(256), stream, b, step);
         }
         if (n_last > 0) {
-            Batch l = b;
-            l.first = first + active - n_last;
-            if (!dev) l.single = host[l.first];
-            l.count = n_last;
-            for (int i = 0; i < n_last; ++i) l.prefix[i + 1] = l.prefix[i] + tri_tiles(host[l.first + i].dim);
+            Batch l;
+            fill_batch(l, h + active - n_last, n_last);
+            l.prefix[0] = 0;
+            for (int i = 0; i < n_last; ++i) l.prefix[i + 1] = l.prefix[i] + tri_tiles(h[active - n_last + i].dim);
             KFAC_LAUNCH(inv_update_kernel<true>, dim3(l.prefix[n_last]), dim3(256), stream, l, step);
         }
     }
@@ -673,26 +936,37 @@ extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, f
     if (nblk_of(dim) > 1) {
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < ws_bytes_of(dim)) return KFAC_ERR_WORKSPACE;
     }
-    return run_group(&it, nullptr, 0, 1, (hipStream_t)stream);
+    return run_group(&it, 1, (hipStream_t)stream);
 }
 
-extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, const kfac_inverse_item* items_dev,
-                                           int32_t count, void* stream) {
-    if (!items_host || !items_dev || count <= 0) return KFAC_ERR_INVALID_ARG;
+extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, int32_t count, void* stream) {
+    if (!items_host || count <= 0) return KFAC_ERR_INVALID_ARG;
     for (int i = 0; i < count; ++i) {
         if (!item_ok(items_host[i])) return KFAC_ERR_INVALID_ARG;
         if (i > 0 && items_host[i].dim > items_host[i - 1].dim) return KFAC_ERR_INVALID_ARG;   // sorted, largest first
     }
-    for (int first = 0; first < count; first += MAXB) {
-        int n = count - first < MAXB ? count - first : MAXB;
-        int rc = run_group(items_host, items_dev, first, n, (hipStream_t)stream);
+    // Matrices beyond what one launch's argument block can describe go into further groups.  Dealing them round
+    // robin keeps every group's size mix (and hence its step count and load) similar.
+    const int ngroups = (count + MAXB - 1) / MAXB;
+    for (int g = 0; g < ngroups; ++g) {
+        kfac_inverse_item sel[MAXB];
+        int n = 0;
+        for (int i = g; i < count; i += ngroups) sel[n++] = items_host[i];
+        int rc = run_group(sel, n, (hipStream_t)stream);
         if (rc != KFAC_OK) return rc;
     }
     return KFAC_OK;
 }
 
 #ifdef KFAC_TILE_TRACE
-extern "C" int kfac_debug_trace_read(unsigned long long* host, size_t n) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(kfac::g_trace), n * sizeof(unsigned long long)) == hipSuccess ? 0 : -4;
+// Debug builds only: copies the tile-phase timestamps to the host and clears them.
+extern "C" int kfac_debug_trace_read(unsigned long long* host, size_t count) {
+    if (count > 4096 * 16) return KFAC_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return KFAC_ERR_HIP;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(kfac::g_trace), count * sizeof(unsigned long long)) != hipSuccess) return KFAC_ERR_HIP;
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(kfac::g_trace)) != hipSuccess) return KFAC_ERR_HIP;
+    if (hipMemset(p, 0, 4096 * 16 * sizeof(unsigned long long)) != hipSuccess) return KFAC_ERR_HIP;
+    return KFAC_OK;
 }
 #endif

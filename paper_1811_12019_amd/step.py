@@ -50,7 +50,8 @@ class KfacNetworkStep:
     damped inverses (optionally skipped: stale inverses) and preconditioning for every layer."""
 
     def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
-                 decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda"):
+                 decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda",
+                 inverse_streams: int = 3):
         self.decay = decay
         self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
         self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
@@ -67,7 +68,21 @@ class KfacNetworkStep:
         dst = []
         for l in self.layers:
             dst += [l.A_inv, l.G_inv]
-        self.inv_batch = kb.InverseBatch(src, dst, [self.damping] * len(src), device=device)
+        # The inversions are independent, so they are dealt (largest first, to the least loaded group, by d^3) into a
+        # few groups that run on streams of their own: the latency-bound pivot/panel kernels of one group then overlap
+        # with the throughput-bound rank-128 updates of the others.
+        n_groups = max(1, min(inverse_streams, len(src)))
+        order_by_size = sorted(range(len(src)), key=lambda i: -src[i].shape[0])
+        groups, load = [[] for _ in range(n_groups)], [0.0] * n_groups
+        for i in order_by_size:
+            g = load.index(min(load))
+            groups[g].append(i)
+            load[g] += float(src[i].shape[0]) ** 3
+        self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [self.damping] * len(grp),
+                                            device=device)
+                            for grp in groups if grp]
+        self.inv_streams = [torch.cuda.Stream(device=device) for _ in self.inv_batches[1:]]
+        self.overlap_inversions = True      # False: run the groups one after the other on the caller's stream
 
     # -- stages ------------------------------------------------------------------------------
     def build_factors(self, stream=None):
@@ -81,7 +96,27 @@ class KfacNetworkStep:
             kb.kfac_ema(l.G_run, l.G_new, l.shape.d_G, self.decay, stream)
 
     def invert(self, stream=None):
-        kb.kfac_damped_inverse_batched(self.inv_batch, stream)
+        main = torch.cuda.current_stream() if stream is None else stream
+        if len(self.inv_batches) == 1 or not self.overlap_inversions:
+            for batch in self.inv_batches:
+                kb.kfac_damped_inverse_batched(batch, main)
+            return
+        fork = torch.cuda.Event()
+        fork.record(main)
+        joins = []
+        for batch, side in zip(self.inv_batches[1:], self.inv_streams):
+            side.wait_event(fork)
+            kb.kfac_damped_inverse_batched(batch, side)
+            done = torch.cuda.Event()
+            done.record(side)
+            joins.append(done)
+        kb.kfac_damped_inverse_batched(self.inv_batches[0], main)
+        for done in joins:
+            main.wait_event(done)
+
+    def inverse_info(self) -> torch.Tensor:
+        """Status words of all inversions (0 = positive definite)."""
+        return torch.cat([b.info for b in self.inv_batches])
 
     def precondition(self, stream=None):
         kb.kfac_precondition_batched(self.pre_batch, stream)

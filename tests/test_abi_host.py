@@ -91,8 +91,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     items = (kb.kfac_inverse_item * 2)()
     items[0] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 64, 0.1)
     items[1] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 300, 0.1)       # not sorted largest-first
-    assert lib.kfac_damped_inverse_batched(items, fake, 2, None) == kb.KFAC_ERR_INVALID_ARG
-    assert lib.kfac_damped_inverse_batched(items, fake, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse_batched(items, 2, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse_batched(items, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse_batched(None, 1, None) == kb.KFAC_ERR_INVALID_ARG
 
     pit = (kb.kfac_precond_item * 1)()
     pit[0] = kb.kfac_precond_item(0x1000, 0x2000, 0x3000, 0x3000, 0x4000, 4, 5)      # out aliases gradW

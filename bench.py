@@ -34,7 +34,6 @@ def kernel_work(net: kstep.KfacNetworkStep):
     """Algorithmic work of each kernel over ONE step of the whole network: (bound, peak, unit, amount)."""
     shapes = [l.shape for l in net.layers]
     dims = [d for s in shapes for d in (s.d_A, s.d_G)]
-    fac = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in shapes)
 
     def is_plain(s):
         return s.kh == 1 and s.kw == 1 and s.stride == 1 and s.pad == 0
@@ -44,12 +43,15 @@ def kernel_work(net: kstep.KfacNetworkStep):
     fac_plain = (sum(kstep.factor_flops(s.R, s.d_A) for s in mfma_ok if is_plain(s)) +
                  sum(kstep.factor_flops(s.R, s.d_G) for s in shapes))
     w = {
-        "inv_update_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops(d) for d in dims)),
+        "inv_update_kernel<false>": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[0] for d in dims)),
+        "inv_update_kernel<true>": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[1] for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
-        "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s", fac),
+        "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
+                                  sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),
         "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),
         "factor_dma_kernel<plain>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_plain),
         "kfac::ema_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
+        "kfac::ema_batched_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
     }
     return w
 

@@ -104,6 +104,16 @@ int kfac_factor_batched(const kfac_factor_item* items_host, const kfac_factor_it
 /* running[dim x dim] <- decay * running + (1 - decay) * fresh, in place.  running and fresh must not overlap. */
 int kfac_ema(float* running, const float* fresh, int32_t dim, float decay, void* stream);
 
+/* The same update for `count` matrices in as few launches as possible (one per 128 matrices).  The array is
+ * read on the host during the call and may be freed afterwards; every pointer in it is a device pointer. */
+typedef struct kfac_ema_item {
+    float* running;      /* dim x dim, updated in place */
+    const float* fresh;  /* dim x dim */
+    int32_t dim;
+} kfac_ema_item;
+
+int kfac_ema_batched(const kfac_ema_item* items_host, int32_t count, float decay, void* stream);
+
 /* Workspace for kfac_damped_inverse of one dim x dim matrix. */
 size_t kfac_inverse_workspace_bytes(int32_t dim);
 

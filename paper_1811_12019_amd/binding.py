@@ -27,7 +27,7 @@ KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 
 EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
-    "kfac_ema",
+    "kfac_ema", "kfac_ema_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -42,6 +42,10 @@ class kfac_layer_desc(ctypes.Structure):
 class kfac_factor_item(ctypes.Structure):
     _fields_ = [("desc", kfac_layer_desc), ("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t), ("scale", ctypes.c_float), ("op", ctypes.c_int32)]
+
+
+class kfac_ema_item(ctypes.Structure):
+    _fields_ = [("running", ctypes.c_void_p), ("fresh", ctypes.c_void_p), ("dim", ctypes.c_int32)]
 
 
 class kfac_inverse_item(ctypes.Structure):
@@ -88,6 +92,8 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_factor_batched.argtypes = [ctypes.POINTER(kfac_factor_item), vp, i32, vp]
     lib.kfac_ema.restype = ctypes.c_int
     lib.kfac_ema.argtypes = [vp, vp, i32, f32, vp]
+    lib.kfac_ema_batched.restype = ctypes.c_int
+    lib.kfac_ema_batched.argtypes = [ctypes.POINTER(kfac_ema_item), i32, f32, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
@@ -202,6 +208,24 @@ def kfac_factor_batched(batch: FactorBatch, stream=None) -> None:
 def kfac_ema(running: torch.Tensor, fresh: torch.Tensor, dim: int, decay: float, stream=None) -> torch.Tensor:
     _check(load_library().kfac_ema(_ptr(running), _ptr(fresh), int(dim), float(decay), _stream(stream)), "kfac_ema")
     return running
+
+
+class EmaBatch:
+    """A kfac_ema_item table (host memory; built once, reused every step)."""
+
+    def __init__(self, running: Sequence[torch.Tensor], fresh: Sequence[torch.Tensor]):
+        n = len(running)
+        self.count = n
+        self.keep = (list(running), list(fresh))
+        arr = (kfac_ema_item * max(n, 1))()
+        for i in range(n):
+            arr[i] = kfac_ema_item(running[i].data_ptr(), fresh[i].data_ptr(), int(running[i].shape[0]))
+        self.host = arr
+
+
+def kfac_ema_batched(batch: EmaBatch, decay: float, stream=None) -> None:
+    rc = load_library().kfac_ema_batched(batch.host, batch.count, float(decay), _stream(stream))
+    _check(rc, "kfac_ema_batched")
 
 
 def kfac_inverse_workspace_bytes(dim: int) -> int:

@@ -62,6 +62,8 @@ class KfacNetworkStep:
         self.factor_batch = kb.FactorBatch(builds, device=device)
         self.pre_batch = kb.PrecondBatch([l.G_inv for l in self.layers], [l.A_inv for l in self.layers],
                                          [l.gradW for l in self.layers], [l.P for l in self.layers], device=device)
+        self.ema_batch = kb.EmaBatch([t for l in self.layers for t in (l.A_run, l.G_run)],
+                                     [t for l in self.layers for t in (l.A_new, l.G_new)])
         src = []
         for l in self.layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
@@ -91,9 +93,7 @@ class KfacNetworkStep:
     def update_running(self, stream=None):
         if self.decay is None:
             return
-        for l in self.layers:
-            kb.kfac_ema(l.A_run, l.A_new, l.shape.d_A, self.decay, stream)
-            kb.kfac_ema(l.G_run, l.G_new, l.shape.d_G, self.decay, stream)
+        kb.kfac_ema_batched(self.ema_batch, self.decay, stream)
 
     def invert(self, stream=None):
         main = torch.cuda.current_stream() if stream is None else stream
@@ -150,12 +150,23 @@ def precondition_flops(dG: int, dA: int) -> float:
 INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
 
 
-def inverse_update_flops(dim: int) -> float:
-    """Flops of the rank-b updates of the blocked sweep (triangle of the part outside each pivot block)."""
-    total, k0 = 0.0, 0
+def inverse_update_flops_split(dim: int):
+    """Flops of the rank-b updates of the blocked sweep (triangle of the part outside each pivot block):
+    (all steps but the matrix's last, the last step)."""
+    if dim <= INVERSE_BLOCK:
+        return 0.0, 0.0
+    mid, last, k0 = 0.0, 0.0, 0
     while k0 < dim:
         b = min(INVERSE_BLOCK, dim - k0)
         rest = dim - b
-        total += float(rest) * (rest + 1) * b
+        work = float(rest) * (rest + 1) * b
+        if k0 + b >= dim:
+            last += work
+        else:
+            mid += work
         k0 += b
-    return total if dim > INVERSE_BLOCK else 0.0
+    return mid, last
+
+
+def inverse_update_flops(dim: int) -> float:
+    return sum(inverse_update_flops_split(dim))

@@ -83,6 +83,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_ema(fake, fake, 4, 0.95, None) == kb.KFAC_ERR_INVALID_ARG          # overlap
     assert lib.kfac_ema(fake, ctypes.c_void_p(0x9000), 4, 1.5, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_ema(fake, ctypes.c_void_p(0x9000), 0, 0.5, None) == kb.KFAC_ERR_INVALID_ARG
+    items = (kb.kfac_ema_item * 2)(kb.kfac_ema_item(0x1000, 0x9000, 4), kb.kfac_ema_item(0x1000, 0x1000, 4))
+    assert lib.kfac_ema_batched(items, 2, 0.95, None) == kb.KFAC_ERR_INVALID_ARG        # second item overlaps
+    assert lib.kfac_ema_batched(None, 1, 0.95, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_ema_batched(items, 1, -0.1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_ema_batched(items, 0, 0.95, None) == kb.KFAC_OK                     # nothing to do, no launch
 
     assert lib.kfac_damped_inverse(fake, 0, 0.1, ctypes.c_void_p(0x9000), None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse(fake, 8, 0.1, fake, None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG   # in place

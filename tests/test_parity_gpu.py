@@ -177,6 +177,25 @@ def test_ema(dim):
     np.testing.assert_allclose(St.cpu().numpy(), want, rtol=0, atol=1e-6 * np.abs(want).max())
 
 
+@pytest.mark.gpu
+def test_ema_batched_mixed_sizes():
+    """One launch over many matrices: chunk boundaries (4096 elements), ragged tails, a 1 x 1 matrix, more
+    matrices than one launch carries (128)."""
+    dims = [1, 3, 64, 65, 127, 128, 577, 1025] + [5 + (i % 7) for i in range(130)]
+    rng = np.random.default_rng(11)
+    S = [rng.standard_normal((d, d)).astype(np.float32) for d in dims]
+    X = [rng.standard_normal((d, d)).astype(np.float32) for d in dims]
+    St = [torch.from_numpy(a).to(DEV) for a in S]
+    Xt = [torch.from_numpy(a).to(DEV) for a in X]
+    kb.kfac_ema_batched(kb.EmaBatch(St, Xt), 0.95)
+    torch.cuda.synchronize()
+    for s, x, st, xt in zip(S, X, St, Xt):
+        want = ko.ema(s, x, np.float32(0.95))
+        np.testing.assert_allclose(st.cpu().numpy(), want, rtol=0, atol=2e-7 * max(np.abs(want).max(), 1.0))
+        np.testing.assert_array_equal(xt.cpu().numpy(), x)          # the fresh factor is only read
+    kb.kfac_ema_batched(kb.EmaBatch([], []), 0.95)                   # empty batch: nothing to do
+
+
 # ----------------------------------------------------------------------------------------------
 # damped inverse
 # ----------------------------------------------------------------------------------------------

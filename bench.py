@@ -56,6 +56,21 @@ def kernel_work(net: kstep.KfacNetworkStep):
     return w
 
 
+def measured_traffic(kernel: str, batch: int):
+    """HBM bytes per launch of `kernel` as rocprofv3's FETCH_SIZE + WRITE_SIZE counters measured them on this
+    workload (scaled by a copy kernel of known size); the figure is kept with the profile summaries.  None when no
+    summary covers this kernel and batch size."""
+    import re
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_resnet50_b32_step.md")
+    if batch != 32 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\|\s*`?([^|`]+?)`?\s*\|.*\|\s*([0-9.]+)\s*\|\s*$", line)
+        if m and m.group(1).strip() == kernel:
+            return {"bytes_per_launch": float(m.group(2)), "source": "profiles/hbm_traffic_resnet50_b32_step.md"}
+    return None
+
+
 def timed_steps(net, steps):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -122,6 +137,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch three plain 1 GiB -> 1 GiB element-wise copies (torch.neg), for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the per-GPU K-FAC step on ONE GPU; this build has no multi-GPU path "
@@ -152,6 +170,14 @@ def main():
     infos = net.inverse_info().cpu()
     assert int(infos.abs().max()) == 0, "an inversion reported a non-positive-definite factor"
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.neg(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     work = kernel_work(net)
     per_kernel = {}
     for name, (tot_ms, n) in report.items():
@@ -165,8 +191,9 @@ def main():
         per_kernel[name] = e
     dominant = max(report, key=lambda k: report[k][0])
     dom = per_kernel[dominant]
+    traffic = measured_traffic(dominant, args.batch)
     roofline = {"kernel": dominant, "bound": dom.get("bound"), "achieved": dom.get("achieved"), "peak": dom.get("peak"),
-                "unit": dom.get("unit"), "frac": dom.get("frac"), "traffic": None,
+                "unit": dom.get("unit"), "frac": dom.get("frac"), "traffic": traffic,
                 "avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"]}
 
     fac_flops = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in layers)

@@ -249,11 +249,17 @@ static __host__ __device__ bool dma_eligible(const Unfold& u) {
     return u.R < (1 << 24);
 }
 
-static __host__ __device__ FactorPlan plan_dma(const Unfold& u) {
+// `target`: workgroups wanted for this build.  A build launched alone wants about two per CU; in a batched launch
+// the other builds fill the chip, and fewer, longer row splits mean fewer partial sums through HBM.
+constexpr int FTARGET_ALONE = 512;
+constexpr int FTARGET_BATCHED_PLAIN = 128;   // measured best on the 54-layer ResNet-50 batch
+constexpr int FTARGET_BATCHED_CONV = 64;
+
+static __host__ __device__ FactorPlan plan_dma(const Unfold& u, int target = FTARGET_ALONE) {
     FactorPlan p;
     p.tiles_dim = ceil_div(u.d, FT);
     p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
-    int want = 512 / p.ntiles;             // about two workgroups per CU
+    int want = target / p.ntiles;
     int max_split = u.R / (8 * 64);        // at least 512 rows per workgroup
     int ns = want < max_split ? want : max_split;
     if (ns < 1) ns = 1;
@@ -271,6 +277,7 @@ struct FBatch {
     const kfac_factor_item* table;   // device table, or nullptr -> `single`
     kfac_factor_item single;
     int count;
+    int target;                      // plan_dma's workgroup target for every build of this launch
     int index[FMAXB];                // table index of the i-th build of this launch
     int prefix[FMAXB + 1];           // workgroup prefix sums
 };
@@ -293,7 +300,7 @@ __global__ __launch_bounds__(256) void factor_dma_kernel(FBatch b) {
     const kfac_factor_item it = b.table ? b.table[b.index[m]] : b.single;
     Unfold u;
     if (it.op == KFAC_OP_FACTOR_A) make_unfold_A(&it.desc, &u); else make_unfold_G(&it.desc, &u);
-    const FactorPlan p = plan_dma(u);
+    const FactorPlan p = plan_dma(u, b.target);
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     factor_dma_tile<PLAIN, F16>(u, (const KFAC_AS1 unsigned char*)it.x, scale, as_global(it.out),
                                 as_global((float*)it.ws), p.rows_per_split, p.ntiles, p.nsplit, local, smem);
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(256) void factor_reduce_batched_kernel(FBatch b) {
     const kfac_factor_item it = b.table ? b.table[b.index[m]] : b.single;
     Unfold u;
     if (it.op == KFAC_OP_FACTOR_A) make_unfold_A(&it.desc, &u); else make_unfold_G(&it.desc, &u);
-    const FactorPlan p = plan_dma(u);
+    const FactorPlan p = plan_dma(u, b.target);
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     constexpr int SUBS = (FT / 32) * (FT / 32);
     factor_reduce_block<FT>(as_global((const float*)it.ws), p.nsplit, p.ntiles, local / SUBS, local % SUBS, u.d, scale,
@@ -370,12 +377,20 @@ static int run_factor_items(const kfac_factor_item* host, const kfac_factor_item
         if (rc != KFAC_OK) return rc;
     }
     // variants: 0 plain bf16, 1 plain f16, 2 conv bf16, 3 conv f16
+    int n_dma = 0;
+    for (int i = 0; i < count; ++i) {
+        Unfold u;
+        item_unfold(host[i], &u);
+        if (dma_eligible(u) && ((uintptr_t)host[i].x & 15) == 0) ++n_dma;
+    }
     for (int variant = 0; variant < 4; ++variant) {
+        const int target = n_dma < 16 ? FTARGET_ALONE : variant < 2 ? FTARGET_BATCHED_PLAIN : FTARGET_BATCHED_CONV;
         int next = 0;
         while (next < count) {
             FBatch b, r;
             b.table = r.table = dev;
             b.count = r.count = 0;
+            b.target = r.target = target;
             b.prefix[0] = r.prefix[0] = 0;
             for (; next < count && b.count < FMAXB; ++next) {
                 Unfold u;
@@ -384,7 +399,7 @@ static int run_factor_items(const kfac_factor_item* host, const kfac_factor_item
                 const bool plain = u.kh == 1 && u.kw == 1 && u.stride == 1 && u.pad == 0;
                 const bool f16 = u.dtype == KFAC_F16;
                 if ((plain ? 0 : 2) + (f16 ? 1 : 0) != variant) continue;
-                const FactorPlan p = plan_dma(u);
+                const FactorPlan p = plan_dma(u, target);
                 b.index[b.count] = next;
                 b.prefix[b.count + 1] = b.prefix[b.count] + p.ntiles * p.nsplit;
                 if (!dev) b.single = host[next];

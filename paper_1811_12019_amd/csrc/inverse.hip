@@ -824,8 +824,15 @@ template <bool LAST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b, int step) {
     __shared__ __attribute__((aligned(1024))) float lds[UNS * USTAGE / 4];
     TR(0);
+    // Workgroups go to the 8 XCDs round-robin (id % 8) and each XCD has an L2 of its own.  XCD x therefore takes the
+    // x-th contiguous eighth of the tile list (matrix by matrix, row-major over the lower triangle): tiles that
+    // share a T panel (same block row) and mostly the same U panels run on the same L2 instead of all eight.
+    const int total = b.prefix[b.count];
+    const int per_xcd = (total + 7) >> 3;
+    const int lin = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || lin >= total) return;
     int m, tile;
-    locate(b, blockIdx.x, m, tile);
+    locate(b, lin, m, tile);
     const Item it = get_item(b, m);
     int I, J;
     tri_decode(tile, I, J);
@@ -861,6 +868,8 @@ static void fill_batch(Batch& b, const kfac_inverse_item* items, int count) {
 }
 
 // items must be sorted by non-increasing dim (checked by the caller of this function).
+static inline int xcd_grid(int tiles) { return 8 * ((tiles + 7) / 8); }   // eight equal shares, the last one padded
+
 static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) {
     Batch b;
     const int max_steps = nblk_of(h[0].dim);
@@ -893,14 +902,14 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
         if (active > n_last) {
             b.count = active - n_last;
             for (int i = 0; i < b.count; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-            KFAC_LAUNCH(inv_update_kernel<false>, dim3(b.prefix[b.count]), dim3(256), stream, b, step);
+            KFAC_LAUNCH(inv_update_kernel<false>, dim3(xcd_grid(b.prefix[b.count])), dim3(256), stream, b, step);
         }
         if (n_last > 0) {
             Batch l;
             fill_batch(l, h + active - n_last, n_last);
             l.prefix[0] = 0;
             for (int i = 0; i < n_last; ++i) l.prefix[i + 1] = l.prefix[i] + tri_tiles(h[active - n_last + i].dim);
-            KFAC_LAUNCH(inv_update_kernel<true>, dim3(l.prefix[n_last]), dim3(256), stream, l, step);
+            KFAC_LAUNCH(inv_update_kernel<true>, dim3(xcd_grid(l.prefix[n_last])), dim3(256), stream, l, step);
         }
     }
     return KFAC_OK;

@@ -133,6 +133,39 @@ def test_factor_batched_matches_single_calls():
                                                                   kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C))
 
 
+def test_factor_batched_many_builds_use_coarser_row_splits():
+    """With 16 or more matrix-core builds in one call the library splits each build over fewer, longer row ranges
+    than it does for a build on its own (fewer partial sums through HBM): same factors to rounding, not bit for bit.
+    Shapes with enough rows for the two plans to differ: 12,800 and 9,248 unfolded rows."""
+    shapes = [synth.LayerShape("b3x3", 8, 48, 40, 40, 72, 3, 3, 1, 1),
+              synth.LayerShape("b1x1", 8, 136, 34, 34, 200, 1, 1, 1, 0)]
+    builds, keep = [], []
+    for rep in range(5):
+        for i, shp in enumerate(shapes):
+            desc = kb.make_desc(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+            act = synth.round_to_bf16(synth.make_act(shp, 20 + 2 * rep + i))
+            gout = synth.round_to_bf16(synth.make_gout(shp, 20 + 2 * rep + i))
+            at = kb.to_device_tensor(act, kb.KFAC_NHWC, kb.KFAC_BF16, DEV)
+            gt = kb.to_device_tensor(gout, kb.KFAC_NHWC, kb.KFAC_BF16, DEV)
+            A = torch.full((shp.d_A, shp.d_A), float("nan"), device=DEV)
+            G = torch.full((shp.d_G, shp.d_G), float("nan"), device=DEV)
+            builds += [(kb.KFAC_OP_FACTOR_A, desc, at, A, 0.0), (kb.KFAC_OP_FACTOR_G, desc, gt, G, 0.0)]
+            keep.append((shp, act, gout, A, G))
+    assert len(builds) == 20
+    kb.kfac_factor_batched(kb.FactorBatch(builds, device=DEV))
+    torch.cuda.synchronize()
+    for n, (shp, act, gout, A, G) in enumerate(keep):
+        A, G = A.cpu().numpy(), G.cpu().numpy()
+        np.testing.assert_array_equal(A, A.T)
+        np.testing.assert_array_equal(G, G.T)
+        if n < 4:      # the oracle on the first of each kind (and their repeats with other seeds against single calls)
+            assert rel_fro(A, ko.factor_A(act, shp.kh, shp.kw, shp.stride, shp.pad, True, ko.ORDER_KH_KW_C)) < FACTOR_TOL
+            assert rel_fro(G, ko.factor_G(gout)) < FACTOR_TOL
+        A1 = gpu_factor(kb.KFAC_OP_FACTOR_A, shp, act, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+        G1 = gpu_factor(kb.KFAC_OP_FACTOR_G, shp, gout, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+        assert rel_fro(A, A1) < 1e-5 and rel_fro(G, G1) < 1e-5       # fp32 summation order only
+
+
 def test_factor_scale_argument():
     shp = SMALL_SHAPES[0]
     act = synth.round_to_bf16(synth.make_act(shp, 2))

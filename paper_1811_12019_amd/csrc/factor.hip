@@ -14,6 +14,7 @@
 #include "common.h"
 #include "factor_mfma.h"
 #include "factor_dma.h"
+#include "factor_gather.h"
 
 namespace kfac {
 
@@ -270,6 +271,27 @@ static __host__ __device__ FactorPlan plan_dma(const Unfold& u, int target = FTA
     return p;
 }
 
+// Narrow 16-bit NHWC layers the LDS-DMA kernel cannot take (channels not a multiple of 8) with many rows.
+static bool gather_eligible(const Unfold& u) {
+    if (u.dtype != KFAC_BF16 && u.dtype != KFAC_F16) return false;
+    if (u.layout != KFAC_NHWC || (u.C & 7) == 0) return false;
+    if (u.order != KFAC_ORDER_KH_KW_C && !(u.kh == 1 && u.kw == 1)) return false;
+    return u.d <= GA_DMAX && u.R >= 4096 && u.R < (1 << 24);
+}
+
+static FactorPlan plan_gather(const Unfold& u) {
+    FactorPlan p;
+    p.tiles_dim = ceil_div(u.d, GA_T);
+    p.ntiles = p.tiles_dim * (p.tiles_dim + 1) / 2;
+    int ns = u.R / (4 * GA_ROWS);                   // at least 256 rows per workgroup
+    if (ns > 512) ns = 512;                         // two workgroups per CU
+    if (ns < 1) ns = 1;
+    p.rows_per_split = ceil_div(ceil_div(u.R, ns), GA_ROWS) * GA_ROWS;
+    p.nsplit = ceil_div(u.R, p.rows_per_split);
+    p.ws_bytes = (size_t)p.nsplit * p.ntiles * GA_T * GA_T * sizeof(float);
+    return p;
+}
+
 // ---- batched launches: many factor builds in one grid -------------------------------------------------------------
 constexpr int FMAXB = 120;
 
@@ -329,7 +351,10 @@ static bool item_unfold(const kfac_factor_item& it, Unfold* u) {
 static size_t item_ws_bytes(const Unfold& u) {
     size_t a = plan_generic(u).ws_bytes;                       // either kernel may serve the build
     size_t b = dma_eligible(u) ? plan_dma(u).ws_bytes : 0;
-    return align_up(a > b ? a : b, 256);
+    size_t c = gather_eligible(u) ? plan_gather(u).ws_bytes : 0;
+    if (b > a) a = b;
+    if (c > a) a = c;
+    return align_up(a, 256);
 }
 
 static int check_item(const kfac_factor_item& it, Unfold* u) {
@@ -356,7 +381,21 @@ static int launch_dma_group(const FBatch& b, hipStream_t stream) {
     return KFAC_OK;
 }
 
+static int run_gather(const Unfold& u, const kfac_factor_item& it, hipStream_t stream) {
+    const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
+    const FactorPlan p = plan_gather(u);
+    if (u.dtype == KFAC_F16) {
+        KFAC_LAUNCH(factor_gather_kernel<true>, dim3(p.nsplit), dim3(256), stream, u, it.x, (float*)it.ws, p.rows_per_split);
+    } else {
+        KFAC_LAUNCH(factor_gather_kernel<false>, dim3(p.nsplit), dim3(256), stream, u, it.x, (float*)it.ws, p.rows_per_split);
+    }
+    KFAC_LAUNCH(factor_gather_reduce_kernel, dim3(p.ntiles * GA_T), dim3(256), stream, (const float*)it.ws, p.nsplit, p.ntiles,
+                u.d, scale, it.out);
+    return KFAC_OK;
+}
+
 static int run_generic(const Unfold& u, const kfac_factor_item& it, hipStream_t stream) {
+    if (gather_eligible(u) && ((uintptr_t)it.x & 1) == 0) return run_gather(u, it, stream);
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     FactorPlan p = plan_generic(u);
     dim3 grid(p.ntiles, p.nsplit);

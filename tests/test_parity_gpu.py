@@ -106,6 +106,21 @@ def test_factors_resnet_layers_full_size(name):
     check_factor_pair(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C, seed=5)
 
 
+GATHER_SHAPES = [
+    # narrow layers (channels not a multiple of 8) with thousands of rows: the gather-based matrix-core kernel
+    synth.LayerShape("g7x7s2", 4, 3, 70, 70, 16, 7, 7, 2, 3, relu_input=False),      # 4,900 rows, 148 columns
+    synth.LayerShape("g3x3c5", 3, 5, 48, 50, 8, 3, 3, 1, 1),                         # 7,200 rows, 46 columns
+    synth.LayerShape("g1x1c17", 2, 17, 50, 47, 8, 1, 1, 1, 0),                       # 4,700 rows, 18 columns
+    synth.LayerShape("g5x5nobias", 2, 6, 52, 52, 8, 5, 5, 1, 2, has_bias=False),     # 5,408 rows, 150 columns
+]
+
+
+@pytest.mark.parametrize("shape", GATHER_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("dtype", [kb.KFAC_BF16, kb.KFAC_F16])
+def test_factors_narrow_layers(shape, dtype):
+    check_factor_pair(shape, kb.KFAC_NHWC, dtype, kb.KFAC_ORDER_KH_KW_C, seed=3)
+
+
 def test_factor_batched_matches_single_calls():
     """A mixed batch (1x1, 3x3, strided, fc, a layer only the generic kernel serves) equals the single calls bit for bit."""
     shapes = [SMALL_SHAPES[0], SMALL_SHAPES[1], SMALL_SHAPES[3], SMALL_SHAPES[4], SMALL_SHAPES[5], SMALL_SHAPES[2]]

@@ -420,3 +420,66 @@ def test_layer_step_config0_end_to_end():
     assert rel_fro(A_inv.cpu().numpy(), ref["A_inv"]) < INV_TOL
     assert rel_fro(G_inv.cpu().numpy(), ref["G_inv"]) < INV_TOL
     assert rel_fro(P.cpu().numpy(), ref["P"]) < PRE_TOL
+
+
+# ----------------------------------------------------------------------------------------------
+# whole-network step (the object bench.py times), with a stale-inverse schedule
+# ----------------------------------------------------------------------------------------------
+NET_LAYERS = [
+    synth.LayerShape("n.conv1", 4, 3, 70, 70, 16, 7, 7, 2, 3, relu_input=False),    # narrow-layer kernel, 4,900 rows
+    synth.LayerShape("n.3x3", 4, 16, 14, 14, 24, 3, 3, 1, 1),
+    synth.LayerShape("n.1x1", 4, 24, 14, 14, 40, 1, 1, 1, 0),
+    synth.LayerShape("n.3x3s2", 4, 40, 14, 14, 48, 3, 3, 2, 1),                     # d_A = 361: three 128-blocks
+    synth.LayerShape("n.1x1wide", 4, 48, 7, 7, 136, 1, 1, 1, 0),                    # d_G = 136: two blocks
+    synth.LayerShape("n.fc", 4, 200, 1, 1, 10, 1, 1, 1, 0),
+]
+# End to end the fp32 inverse inherits the fp32 rounding of the factors it is given, amplified by at most the
+# condition number of the damped factor (here <= (trace + lambda) / lambda ~ 2e3 on errors ~1e-6 measured
+# stage-wise): 2e-3 bounds the preconditioned gradient against the all-float64 chain.  Stage by stage, each against
+# the oracle fed the GPU stage's own input, the bars are the usual ones.
+END_TO_END_TOL = 2e-3
+
+
+def test_network_step_with_stale_inverses():
+    """KfacNetworkStep (batched entry points only) over three steps, inverses refreshed on steps 0 and 2 only:
+    every stage of every layer against the oracle, stale inverses untouched on step 1."""
+    from paper_1811_12019_amd import step as kstep
+    decay, gamma = 0.95, 1e-3
+    lam = ko.factor_damping(gamma)
+    net = kstep.KfacNetworkStep(NET_LAYERS, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=decay, gamma=gamma,
+                                seed=3, device=DEV, inverse_streams=2)
+    f64 = lambda t: t.detach().cpu().numpy().astype(np.float64)
+    nchw = lambda t: t.float().permute(0, 3, 1, 2).cpu().numpy().astype(np.float64)
+    chain = [dict(A_run=np.eye(l.shape.d_A), G_run=np.eye(l.shape.d_G)) for l in net.layers]     # all-float64 chain
+    prev_run = [(f64(l.A_run), f64(l.G_run)) for l in net.layers]
+    prev_inv = None
+    for step_no, refresh in enumerate([True, False, True]):
+        for l in net.layers:
+            l.gradW.mul_(1.5)                                         # a different gradient every step
+        net.step(refresh_inverse=refresh)
+        torch.cuda.synchronize()
+        assert int(net.inverse_info().abs().max()) == 0
+        for i, l in enumerate(net.layers):
+            s = l.shape
+            A_new = ko.factor_A(nchw(l.act), s.kh, s.kw, s.stride, s.pad, True, ko.ORDER_KH_KW_C)
+            G_new = ko.factor_G(nchw(l.gout))
+            assert rel_fro(f64(l.A_new), A_new) < FACTOR_TOL, (step_no, s.name)
+            assert rel_fro(f64(l.G_new), G_new) < FACTOR_TOL, (step_no, s.name)
+            # running average from the GPU's own previous value and fresh factor
+            assert rel_fro(f64(l.A_run), ko.ema(prev_run[i][0], f64(l.A_new), decay)) < 1e-6
+            assert rel_fro(f64(l.G_run), ko.ema(prev_run[i][1], f64(l.G_new), decay)) < 1e-6
+            if refresh:
+                assert rel_fro(f64(l.A_inv), ko.damped_inverse(f64(l.A_run), float(np.float32(lam)))) < INV_TOL
+                assert rel_fro(f64(l.G_inv), ko.damped_inverse(f64(l.G_run), float(np.float32(lam)))) < INV_TOL
+            else:
+                np.testing.assert_array_equal(f64(l.A_inv), prev_inv[i][0])
+                np.testing.assert_array_equal(f64(l.G_inv), prev_inv[i][1])
+            assert rel_fro(f64(l.P), ko.precondition(f64(l.G_inv), f64(l.gradW), f64(l.A_inv))) < PRE_TOL
+            # the all-float64 chain
+            c = chain[i]
+            c["A_run"], c["G_run"] = ko.ema(c["A_run"], A_new, decay), ko.ema(c["G_run"], G_new, decay)
+            if refresh:
+                c["A_inv"], c["G_inv"] = ko.damped_inverse(c["A_run"], lam), ko.damped_inverse(c["G_run"], lam)
+            assert rel_fro(f64(l.P), ko.precondition(c["G_inv"], f64(l.gradW), c["A_inv"])) < END_TO_END_TOL
+        prev_run = [(f64(l.A_run), f64(l.G_run)) for l in net.layers]
+        prev_inv = [(f64(l.A_inv), f64(l.G_inv)) for l in net.layers]

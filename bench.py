@@ -28,6 +28,10 @@ from paper_1811_12019_amd import step as kstep        # noqa: E402
 from paper_1811_12019_amd import synth                # noqa: E402
 
 PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, TFLOP/s, GB/s
+# fp32 products computed as sums of bf16 x bf16 MFMAs over split operands: 6 MFMAs per fp32 product with both
+# operands split three ways (the sweep's rank-128 update), 3 with both split two ways (preconditioning)
+PEAK["mfma_bf16x3"] = round(PEAK["mfma_bf16"] / 6, 1)
+PEAK["mfma_bf16x2"] = round(PEAK["mfma_bf16"] / 3, 1)
 
 
 def kernel_work(net: kstep.KfacNetworkStep):
@@ -43,9 +47,11 @@ def kernel_work(net: kstep.KfacNetworkStep):
     fac_plain = (sum(kstep.factor_flops(s.R, s.d_A) for s in mfma_ok if is_plain(s)) +
                  sum(kstep.factor_flops(s.R, s.d_G) for s in shapes))
     w = {
-        "inv_update_kernel<false>": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[0] for d in dims)),
-        "inv_update_kernel<true>": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[1] for d in dims)),
-        "gemm_nt_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
+        "inv_update_kernel<false>": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[0] for d in dims)),
+        # the last step of a matrix is a short product (its last block is the ragged one) plus the dense, mirrored
+        # output: read the lower triangle of the working copy, write d x d
+        "inv_update_kernel<true>": ("hbm", PEAK["hbm"], "GB/s", sum(6.0 * d * d for d in dims if d > kstep.INVERSE_BLOCK)),
+        "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),
         "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),

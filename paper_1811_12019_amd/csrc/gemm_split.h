@@ -1,0 +1,168 @@
+// fp32 "NT" tile product on the bf16 matrix cores: acc[128 x 128] += A[128 x K] . B[128 x K]^T, both operands
+// fp32, row-major, K contiguous.  Each fp32 operand value is split on the fly into NS bf16 pieces
+//     x = x0 + x1 (+ x2),   x0 = bf16(x), x1 = bf16(x - x0), x2 = bf16(x - x0 - x1)
+// (8 significant bits each, so 2 pieces carry 16 bits of x and 3 pieces all 24), and the product is the sum of
+// the bf16 x bf16 MFMAs (exact products, fp32 accumulate) of all piece pairs whose combined order is below NS:
+//     NS = 2:  a0 b0 + a0 b1 + a1 b0                            relative error of a product ~ 2^-16
+//     NS = 3:  a0 b0 + a0 b1 + a1 b0 + a0 b2 + a1 b1 + a2 b0    ~ 2^-23: on a par with fp32 multiply-add
+// v_mfma_f32_32x32x16_bf16 runs at 16 times the rate of v_mfma_f32_32x32x2_f32, so 3 (6) products per fp32
+// product still leave a factor 5.3 (2.7) over the fp32 matrix-core peak.
+//
+// One workgroup = 4 wavefronts in a 2 x 2 arrangement, each owning a 64 x 64 quadrant as 2 x 2 MFMA blocks.  K
+// advances 16 at a time through a double-buffered LDS stage: the next slab is fetched into registers while the
+// current one is multiplied, then split and stored to the other buffer; one barrier per slab.
+// LDS layout per buffer: operand (A, B) x piece x 128 rows x 32 bytes (16 bf16 = the slab's K); the two 16-byte
+// halves of a row are swapped on every other group of 4 rows, which makes the 16-byte MFMA operand reads
+// (32 consecutive rows per half-wave) bank-conflict free.
+#pragma once
+
+#include "factor_mfma.h"
+#include "gemm_f32.h"
+
+namespace kfac {
+
+constexpr int SPLIT_KS = 16;                           // K per LDS stage
+constexpr int SPLIT_PLANE = 128 * 32;                  // bytes of one operand piece per stage
+template <int NS> constexpr int split_lds_bytes() { return 2 * 2 * NS * SPLIT_PLANE; }   // 32 KB (NS=2), 48 KB (NS=3)
+
+typedef __bf16 v2bf_t __attribute__((ext_vector_type(2)));
+typedef float v2f_t __attribute__((ext_vector_type(2)));
+
+// bf16 pieces of four floats: piece[p] holds 4 bf16 (8 bytes) for p < NS
+template <int NS>
+__device__ __forceinline__ void split4(const v4f& x, uint2 (&piece)[NS]) {
+    v4f rem = x;
+#pragma unroll
+    for (int p = 0; p < NS; ++p) {
+        const v2f_t lo2 = {rem.x, rem.y}, hi2 = {rem.z, rem.w};
+        const v2bf_t a = __builtin_convertvector(lo2, v2bf_t), b = __builtin_convertvector(hi2, v2bf_t);
+        unsigned ua, ub;
+        __builtin_memcpy(&ua, &a, 4);
+        __builtin_memcpy(&ub, &b, 4);
+        piece[p] = make_uint2(ua, ub);
+        if (p + 1 < NS) {
+            rem.x -= __uint_as_float(ua << 16);
+            rem.y -= __uint_as_float(ua & 0xffff0000u);
+            rem.z -= __uint_as_float(ub << 16);
+            rem.w -= __uint_as_float(ub & 0xffff0000u);
+        }
+    }
+}
+
+// lds: split_lds_bytes<NS>() bytes, 16-byte aligned.  acc is accumulated into (the caller zeroes it).
+// skip_upper_right: the (wm = 0, wn = 1) quadrant is not needed (diagonal tile of a symmetric result).
+// NEG_A: the product is subtracted (the A operand is negated before it is split).
+// NST > 0: both operands are complete, 16-byte aligned panels (all 128 rows present, K exactly NST * 16): loads are
+// unguarded, every wavefront multiplies, and the stage loop is unrolled completely.  With no branches left the
+// compiler counts the loads in flight exactly instead of draining them at every join, which is what makes the
+// two-stage look-ahead effective.
+template <int NS, bool NEG_A = false, int NST = 0>
+__device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, int lda, int arows,
+                                                  const gfloat* __restrict__ B, int ldb, int brows, int K,
+                                                  unsigned char* __restrict__ lds, TileAcc& acc,
+                                                  bool skip_upper_right = false) {
+    static_assert(NS == 2 || NS == 3, "two or three bf16 pieces");
+    constexpr int BUF = 2 * NS * SPLIT_PLANE;          // bytes per buffer
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    const bool compute = !(skip_upper_right && wm == 0 && wn == 1);
+    // producer: rows lr and lr + 64, floats 4 kq .. 4 kq + 3 of the slab
+    const int lr = t >> 2, kq = t & 3;
+    unsigned w_off[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int row = lr + 64 * p;
+        w_off[p] = (unsigned)(row * 32 + (((kq >> 1) ^ ((row >> 2) & 1)) * 16) + (kq & 1) * 8);
+    }
+    // consumer: byte offsets (inside one piece plane) of this lane's 16 bytes for row blocks 0, 1
+    unsigned a_off[2], b_off[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int ra = wm * 64 + q * 32 + lm, rb = wn * 64 + q * 32 + lm;
+        a_off[q] = (unsigned)(ra * 32 + ((h ^ ((ra >> 2) & 1)) * 16));
+        b_off[q] = (unsigned)(rb * 32 + ((h ^ ((rb >> 2) & 1)) * 16) + NS * SPLIT_PLANE);
+    }
+
+    // Two register sets: the slab two stages ahead is in flight while the current one is multiplied, so a fetch
+    // has two stage times to arrive (the operands of a sweep step were just written by another kernel and come
+    // from beyond the L2).
+    v4f ra[2][2], rb[2][2];
+    auto fetch = [&](int k0, v4f (&xa)[2], v4f (&xb)[2]) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = lr + 64 * p;
+            if constexpr (NST > 0) {
+                xa[p] = *(const KFAC_AS1 v4f*)(A + (size_t)row * lda + k0 + 4 * kq);
+                xb[p] = *(const KFAC_AS1 v4f*)(B + (size_t)row * ldb + k0 + 4 * kq);
+            } else {
+                xa[p] = load4_guard(A + (size_t)row * lda, row < arows, k0 + 4 * kq, K);
+                xb[p] = load4_guard(B + (size_t)row * ldb, row < brows, k0 + 4 * kq, K);
+            }
+        }
+    };
+    auto stash = [&](int buf, const v4f (&xa)[2], const v4f (&xb)[2]) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint2 pa[NS], pb[NS];
+            split4<NS>(NEG_A ? -xa[p] : xa[p], pa);     // negated here, not at the fetch: a use would force the wait early
+            split4<NS>(xb[p], pb);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                *(uint2*)(lds + buf * BUF + s * SPLIT_PLANE + w_off[p]) = pa[s];
+                *(uint2*)(lds + buf * BUF + (NS + s) * SPLIT_PLANE + w_off[p]) = pb[s];
+            }
+        }
+    };
+    auto mma = [&](int buf) {
+        if (NST == 0 && !compute) return;
+        uint4 a[2][NS], b[2][NS];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int p = 0; p < NS; ++p) {
+                a[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + a_off[q]);
+                b[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + b_off[q]);
+            }
+        // smallest terms first
+#pragma unroll
+        for (int order = NS - 1; order >= 0; --order)
+#pragma unroll
+            for (int pa = 0; pa <= order; ++pa)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        acc.c[mb][nb] = mfma16<false>(a[mb][pa], b[nb][order - pa], acc.c[mb][nb]);
+    };
+
+    if constexpr (NST > 0) {
+        fetch(0, ra[0], rb[0]);
+        if (NST > 1) fetch(SPLIT_KS, ra[1], rb[1]);
+        stash(0, ra[0], rb[0]);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            if (s + 2 < NST) fetch((s + 2) * SPLIT_KS, ra[s & 1], rb[s & 1]);
+            mma(s & 1);
+            if (s + 1 < NST) stash((s + 1) & 1, ra[(s + 1) & 1], rb[(s + 1) & 1]);
+            __syncthreads();
+        }
+        return;
+    }
+    // general K: one slab of look-ahead (a second register set only costs occupancy here: inside a loop the
+    // compiler drains all loads at the back edge anyway)
+    const int nst = (K + SPLIT_KS - 1) / SPLIT_KS;
+    fetch(0, ra[0], rb[0]);
+    stash(0, ra[0], rb[0]);
+    __syncthreads();
+    for (int s = 0; s < nst; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < nst) fetch((s + 1) * SPLIT_KS, ra[0], rb[0]);
+        mma(buf);
+        if (s + 1 < nst) stash(buf ^ 1, ra[0], rb[0]);
+        __syncthreads();
+    }
+}
+
+}  // namespace kfac

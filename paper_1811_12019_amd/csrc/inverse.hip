@@ -17,7 +17,7 @@
 // lower triangle (tiles on or below the diagonal) up to date: the part of block column k that lies above the
 // pivot block is read, transposed, from block row k.  Only the last step writes the caller's dense output, both
 // triangles, exactly symmetric (the upper one is a copy of the lower one).
-#include "gemm_f32.h"
+#include "gemm_split.h"
 
 namespace kfac {
 
@@ -28,6 +28,9 @@ constexpr int MAXB = 64;         // matrices per launch group (bounded by the 4 
 #endif
 #ifndef UPD_WAVES
 #define UPD_WAVES 3
+#endif
+#ifndef UPD_SPLIT
+#define UPD_SPLIT 1
 #endif
 constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
 constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
@@ -783,6 +786,48 @@ __device__ __forceinline__ void upd_regular_mid(const UpdCtx& c, const gfloat* _
     TR(5);
 }
 
+// Same tile, product on the bf16 matrix cores with both operands split three ways (gemm_split.h): the accumulators
+// start as the tile's old values (fetched straight into MFMA register layout), the negated product is added, and
+// the result is stored from the registers.
+__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfloat* __restrict__ U, unsigned char* __restrict__ lds) {
+    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
+    gfloat* wtile = c.W + (size_t)c.i0 * c.ldw + c.j0;
+    const int rows_left = c.irows - wm * 64 - 4 * h;     // tile rows from the lane's first row on
+    bool colok[2];
+    gfloat* wq[2];
+#pragma unroll
+    for (int nbk = 0; nbk < 2; ++nbk) {
+        colok[nbk] = !dead && c.j0 + wn * 64 + nbk * 32 < c.ldw;
+        wq[nbk] = wtile + (size_t)(wm * 64 + 4 * h) * c.ldw + wn * 64 + nbk * 32 + lm;
+    }
+    TileAcc acc;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? wq[nbk][(size_t)dr * c.ldw] : 0.f;
+            }
+    TR(1);
+    tile_mma_nt_split<3, true, NB / SPLIT_KS>(c.T + (size_t)c.i0 * NB, NB, NB, U + (size_t)c.j0 * NB, NB, NB, NB, lds, acc, c.diag);
+    TR(3);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                if (colok[nbk] && dr < rows_left) wq[nbk][(size_t)dr * c.ldw] = acc.c[mb][nbk][r];
+            }
+    TR(5);
+}
+
 // column tile (from_rows = true): new[a][c] = T[(i0 + a)][c];  row tile: new[a][c] = T[(j0 + c)][a]
 template <bool LAST>
 __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* __restrict__ lds) {
@@ -848,6 +893,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     c.diag = I == J;
     if (I != kb && J != kb) {
         if constexpr (LAST) upd_regular<true>(c, ws.U, lds);
+        else if (UPD_SPLIT) upd_regular_mid_split(c, ws.U, (unsigned char*)lds);
         else upd_regular_mid(c, ws.U, lds);
     }
     else upd_panel<LAST>(c, J == kb, lds);

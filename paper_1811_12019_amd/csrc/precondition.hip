@@ -6,7 +6,7 @@
 //   P [dG x dA] = Ginv . Yt^T         P [i, j] = sum_k Ginv[i, k] Yt[j, k]
 // A batch of layers runs as two launches (one per product) over the tiles of all layers together, so that the
 // many small layers fill the machine; the workgroup -> (layer, tile) map is a prefix table in the kernel arguments.
-#include "gemm_f32.h"
+#include "gemm_split.h"
 
 namespace kfac {
 
@@ -21,7 +21,7 @@ struct PBatch {
 
 // phase 1: Yt[dA x dG] = Ainv . gradW^T      phase 2: out[dG x dA] = Ginv . Yt^T
 __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
-    __shared__ float lds[GEMM_LDS_FLOATS];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[split_lds_bytes<2>()];
     int lo = 0, hi = b.count;
     const int wg = blockIdx.x;
     while (hi - lo > 1) {
@@ -40,7 +40,13 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     const int i0 = ti * TM, j0 = tj * TM;
     const int irows = min(TM, M - i0), jrows = min(TM, N - j0);
     TileAcc acc;
-    tile_mma_nt(A + (size_t)i0 * K, K, irows, B + (size_t)j0 * K, K, jrows, K, lds, acc);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc.c[mb][nb][r] = 0.f;
+    tile_mma_nt_split<2>(A + (size_t)i0 * K, K, irows, B + (size_t)j0 * K, K, jrows, K, lds, acc);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)

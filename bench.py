@@ -47,10 +47,9 @@ def kernel_work(net: kstep.KfacNetworkStep):
     fac_plain = (sum(kstep.factor_flops(s.R, s.d_A) for s in mfma_ok if is_plain(s)) +
                  sum(kstep.factor_flops(s.R, s.d_G) for s in shapes))
     w = {
-        "inv_update_kernel<false>": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_update_flops_split(d)[0] for d in dims)),
-        # the last step of a matrix is a short product (its last block is the ragged one) plus the dense, mirrored
-        # output: read the lower triangle of the working copy, write d x d
-        "inv_update_kernel<true>": ("hbm", PEAK["hbm"], "GB/s", sum(6.0 * d * d for d in dims if d > kstep.INVERSE_BLOCK)),
+        # all steps of all matrices in one kernel; a matrix's last step (short product, dense mirrored output) is a
+        # small part of it
+        "inv_update_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_update_flops(d) for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),

@@ -865,9 +865,11 @@ __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* _
     }
 }
 
-template <bool LAST>
+// One launch per step for all matrices of the batch that still have a block `step`; a matrix whose last block this
+// is takes the output-writing paths (LAST), the others update their working copies.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b, int step) {
     __shared__ __attribute__((aligned(1024))) float lds[UNS * USTAGE / 4];
+    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
     TR(0);
     // Workgroups go to the 8 XCDs round-robin (id % 8) and each XCD has an L2 of its own.  XCD x therefore takes the
     // x-th contiguous eighth of the tile list (matrix by matrix, row-major over the lower triangle): tiles that
@@ -883,6 +885,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     tri_decode(tile, I, J);
     const int kb = step;
     if (I == kb && J == kb) return;             // the pivot block itself was written by inv_pivot_kernel
+    const bool last = nblk_of(it.dim) == step + 1;      // uniform per workgroup
     const WsView ws = ws_view(it.ws, it.dim);
     UpdCtx c;
     c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T; c.out = it.Minv;
@@ -892,11 +895,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     c.nb = min(NB, c.d - step * NB);
     c.diag = I == J;
     if (I != kb && J != kb) {
-        if constexpr (LAST) upd_regular<true>(c, ws.U, lds);
+        if (last) upd_regular<true>(c, ws.U, lds);
         else if (UPD_SPLIT) upd_regular_mid_split(c, ws.U, (unsigned char*)lds);
         else upd_regular_mid(c, ws.U, lds);
+    } else if (last) {
+        upd_panel<true>(c, J == kb, lds);
+    } else {
+        upd_panel<false>(c, J == kb, lds);
     }
-    else upd_panel<LAST>(c, J == kb, lds);
 }
 
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
@@ -942,21 +948,9 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
         KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
         KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
-        // matrices in their final step (they sit at the end of the active range) write the caller's output
-        int n_last = 0;
-        while (n_last < active && nblk_of(h[active - 1 - n_last].dim) == step + 1) ++n_last;
-        if (active > n_last) {
-            b.count = active - n_last;
-            for (int i = 0; i < b.count; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-            KFAC_LAUNCH(inv_update_kernel<false>, dim3(xcd_grid(b.prefix[b.count])), dim3(256), stream, b, step);
-        }
-        if (n_last > 0) {
-            Batch l;
-            fill_batch(l, h + active - n_last, n_last);
-            l.prefix[0] = 0;
-            for (int i = 0; i < n_last; ++i) l.prefix[i + 1] = l.prefix[i] + tri_tiles(h[active - n_last + i].dim);
-            KFAC_LAUNCH(inv_update_kernel<true>, dim3(xcd_grid(l.prefix[n_last])), dim3(256), stream, l, step);
-        }
+        b.count = active;
+        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
+        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(b.prefix[active])), dim3(256), stream, b, step);
     }
     return KFAC_OK;
 }

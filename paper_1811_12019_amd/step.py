@@ -170,3 +170,25 @@ def inverse_update_flops_split(dim: int):
 
 def inverse_update_flops(dim: int) -> float:
     return sum(inverse_update_flops_split(dim))
+
+
+def inverse_pivot_flops(dim: int) -> float:
+    """Flops of the pivot-block inversions of the blocked sweep (b^3 per b x b block)."""
+    total, k0 = 0.0, 0
+    while k0 < dim:
+        b = min(INVERSE_BLOCK, dim - k0)
+        total += float(b) ** 3
+        k0 += b
+    return total
+
+
+def inverse_panel_flops(dim: int) -> float:
+    """Flops of the panel products T = W_:k P of the blocked sweep (every row outside the pivot block)."""
+    if dim <= INVERSE_BLOCK:
+        return 0.0
+    total, k0 = 0.0, 0
+    while k0 < dim:
+        b = min(INVERSE_BLOCK, dim - k0)
+        total += 2.0 * (dim - b) * b * b
+        k0 += b
+    return total

@@ -201,8 +201,10 @@ def main():
     dominant = max(report, key=lambda k: report[k][0])
     dom = per_kernel[dominant]
     traffic = measured_traffic(dominant, args.batch)
+    traffic_bytes = traffic["bytes_per_launch"] if traffic else None
     roofline = {"kernel": dominant, "bound": dom.get("bound"), "achieved": dom.get("achieved"), "peak": dom.get("peak"),
-                "unit": dom.get("unit"), "frac": dom.get("frac"), "traffic": traffic,
+                "unit": dom.get("unit"), "frac": dom.get("frac"), "traffic": traffic_bytes,
+                "traffic_source": traffic["source"] if traffic else None,
                 "avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"]}
 
     fac_flops = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in layers)
@@ -221,7 +223,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_oracle_baseline(
-            net, {"conv1", "layer1.0.conv2", "layer2.1.conv1", "layer3.1.conv2", "layer4.1.conv2", "fc"})
+            net, {"conv1", "layer1.0.conv2", "layer2.1.conv1", "layer3.1.conv2", "layer3.2.conv2", "layer4.0.conv2",
+                  "layer4.1.conv2", "layer4.2.conv2", "layer4.0.downsample", "fc"})
     print(json.dumps(out))
 
 

@@ -314,8 +314,11 @@ __device__ __forceinline__ int fbatch_locate(const FBatch& b, int wg, int& local
     return lo;
 }
 
+#ifndef FACTOR_WAVES
+#define FACTOR_WAVES 2
+#endif
 template <bool PLAIN, bool F16>
-__global__ __launch_bounds__(256) void factor_dma_kernel(FBatch b) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FACTOR_WAVES, 8))) void factor_dma_kernel(FBatch b) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     int local;
     const int m = fbatch_locate(b, blockIdx.x, local);

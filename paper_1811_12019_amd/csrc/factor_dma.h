@@ -4,7 +4,7 @@
 // patch matrix.  The contraction index (unfolded row) is the slow index in memory, and the MFMA wants it
 // contiguous per lane; gfx950 has exactly the two instructions that make this cheap:
 //   * global_load_lds_dwordx4 copies 16 bytes per lane from global memory straight into LDS (lane i lands at
-//     base + 16 i) without passing through registers, so a 4-stage ring of 32-row slabs can be kept in flight
+//     base + 16 i) without passing through registers, so a 3-stage ring of 32-row slabs can be kept in flight
 //     with no register cost and a single barrier per slab;
 //   * ds_read_b64_tr_b16 reads a 16 x 4 block of 16-bit values transposed: within 16 lanes, lane j receives
 //     element (j % 4) of lanes j/4, j/4 + 4, j/4 + 8, j/4 + 12.  With lanes pointed at 4 rows x 4 column groups
@@ -24,10 +24,13 @@
 namespace kfac {
 
 constexpr int DK = 32;                       // unfolded rows per stage
-constexpr int DNS = 4;                       // stages in the ring
+#ifndef FACTOR_DNS
+#define FACTOR_DNS 3
+#endif
+constexpr int DNS = FACTOR_DNS;              // stages in the ring (DNS - 1 in flight)
 constexpr int DPANEL = 8 * 1024;             // bytes per operand panel per stage
 constexpr int DSTAGE = 2 * DPANEL;
-constexpr int FACTOR_DMA_LDS = DNS * DSTAGE; // 65,536 B (the epilogue staging aliases it)
+constexpr int FACTOR_DMA_LDS = DNS * DSTAGE; // 49,152 B (the epilogue staging aliases it)
 
 static __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u};
 static __device__ uint4 g_one_chunk_bf16 = {0x3F80u, 0u, 0u, 0u};
@@ -170,10 +173,9 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[p][q][r] = 0.f;
 
-    // prologue: three stages in flight
-    issue_stage(0, 0);
-    issue_stage(1, 1);
-    issue_stage(2, 2);
+    // prologue: DNS - 1 stages in flight
+#pragma unroll
+    for (int s = 0; s < DNS - 1; ++s) issue_stage(s, s);
 
     for (int it = 0; it < nst; it += DNS) {
 #pragma unroll
@@ -181,9 +183,15 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
             const int s = it + bi;
             if (s >= nst) break;                                   // uniform
             // this thread's DMA for stage s has landed (two later stages may still be in flight) ...
-            if (diag) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");   // ... and so has everybody else's
-            issue_stage(s + 3, (bi + 3) & 3);                      // refill the buffer stage s-1 just vacated
+            if constexpr (DNS == 4) {
+                if (diag) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");   // ... and so has everybody else's
+            } else {
+                static_assert(DNS == 3 || DNS == 4, "ring depth");
+                if (diag) asm volatile("s_waitcnt vmcnt(2)\n\ts_barrier" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+            }
+            issue_stage(s + DNS - 1, (bi + DNS - 1) % DNS);        // refill the buffer stage s-1 just vacated
             if (wave_on) {
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {

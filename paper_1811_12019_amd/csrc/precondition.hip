@@ -6,6 +6,8 @@
 //   P [dG x dA] = Ginv . Yt^T         P [i, j] = sum_k Ginv[i, k] Yt[j, k]
 // A batch of layers runs as two launches (one per product) over the tiles of all layers together, so that the
 // many small layers fill the machine; the workgroup -> (layer, tile) map is a prefix table in the kernel arguments.
+#include <algorithm>
+
 #include "gemm_split.h"
 
 namespace kfac {
@@ -17,6 +19,7 @@ struct PBatch {
     kfac_precond_item single;
     int first, count;
     int prefix[PMAXB + 1];            // workgroup prefix sums over the items of this launch
+    short order[PMAXB];               // launch position -> item (relative to first): longest contraction first
 };
 
 // phase 1: Yt[dA x dG] = Ainv . gradW^T      phase 2: out[dG x dA] = Ginv . Yt^T
@@ -28,7 +31,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
         int mid = (lo + hi) >> 1;
         if (b.prefix[mid] <= wg) lo = mid; else hi = mid;
     }
-    const kfac_precond_item it = b.table ? b.table[b.first + lo] : b.single;
+    const kfac_precond_item it = b.table ? b.table[b.first + b.order[lo]] : b.single;
     const int local = wg - b.prefix[lo];
     const gfloat *A, *B;
     gfloat* C;
@@ -69,9 +72,16 @@ static int run_group(const kfac_precond_item* host, const kfac_precond_item* dev
     b.count = count;
     if (!dev) b.single = host[first];
     for (int phase = 1; phase <= 2; ++phase) {
+        // tiles with the longest contraction (K = dA in phase 1, dG in phase 2) go first: workgroups are dispatched in
+        // order, so the long ones start early and the short ones fill the tail
+        for (int i = 0; i < count; ++i) b.order[i] = (short)i;
+        std::stable_sort(b.order, b.order + count, [&](short x, short y) {
+            const kfac_precond_item &a = host[first + x], &c = host[first + y];
+            return (phase == 1 ? a.dA : a.dG) > (phase == 1 ? c.dA : c.dG);
+        });
         b.prefix[0] = 0;
         for (int i = 0; i < count; ++i) {
-            const kfac_precond_item& it = host[first + i];
+            const kfac_precond_item& it = host[first + b.order[i]];
             b.prefix[i + 1] = b.prefix[i] + (phase == 1 ? tiles_of(it.dA, it.dG) : tiles_of(it.dG, it.dA));
         }
         KFAC_LAUNCH(gemm_nt_kernel, dim3(b.prefix[count]), dim3(256), stream, b, phase);

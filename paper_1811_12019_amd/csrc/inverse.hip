@@ -378,14 +378,27 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
             }
     __syncthreads();
     {
-        const int c = t & 127, rh = t >> 7;
-        if (c < nb) {
-            for (int row = rh; row < nb; row += 2) {
-                const float x = sD[max(row, c) * (NB + 1) + min(row, c)];
-                if (last) it.Minv[(size_t)(k0 + row) * d + k0 + c] = -x;
-                else ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c] = x;
-                if (!from_S) ws.P[row * NB + c] = -x;
+        // thread = four consecutive columns of one row, 8 rows per pass: 16-byte stores (the working copy and the P
+        // buffer are 16-byte aligned; the caller's output need not be)
+        const int c4 = (t & 31) * 4, r0 = t >> 5;
+#pragma unroll 4
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + 8 * p;
+            if (row >= nb || c4 >= nb) continue;
+            v4f x;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = min(c4 + i, nb - 1);
+                x[i] = sD[max(row, c) * (NB + 1) + min(row, c)];
             }
+            if (last) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (c4 + i < nb) it.Minv[(size_t)(k0 + row) * d + k0 + c4 + i] = -x[i];
+            } else {
+                *(KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4] = x;      // a block that is not last is full
+            }
+            if (!from_S) *(KFAC_AS1 v4f*)&ws.P[row * NB + c4] = -x;    // (columns beyond a ragged block are never read)
         }
     }
 }

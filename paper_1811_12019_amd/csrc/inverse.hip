@@ -23,14 +23,8 @@ namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
 constexpr int MAXB = 64;         // matrices per launch group (bounded by the 4 KB of kernel arguments)
-#ifndef UPD_TK
-#define UPD_TK 16
-#endif
 #ifndef UPD_WAVES
 #define UPD_WAVES 3
-#endif
-#ifndef UPD_SPLIT
-#define UPD_SPLIT 1
 #endif
 constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
 constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
@@ -449,7 +443,8 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
 //   row          I == k, J < k:  new[a][c] = T[J*128 + c][a]          (block row k left of the pivot)
 // LAST = false: the tile goes back into the padded working copy (whole 512-byte rows).
 // LAST = true (the matrix's final step): the tile, negated, goes to the caller's output, and so does its mirror image.
-// Every tile passes through an LDS stage, 64 tile rows at a time, so that global accesses are row-wise.
+// Column / row tiles and all tiles of a final step pass through an LDS stage, 64 tile rows at a time, so that global
+// accesses are row-wise; regular tiles of the other steps go from and to registers (upd_regular_mid_split).
 struct UpdCtx {
     gfloat* W; int ldw; const gfloat* T; gfloat* out;
     int d, i0, j0, irows, jrows, nb;
@@ -646,162 +641,10 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
 
 // Regular tile of a step that is not the matrix's last one: new = old - T_I U_J^T goes back into the working copy.
 // Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot block is
-// full: exactly 8 K-slabs, unrolled.  The product accumulates (negated) from zero; the tile's old values are fetched
-// straight into MFMA register layout (register r of a 32 x 32 block: 32 consecutive floats of one row per half-wave)
-// in two halves of 32 registers while the slabs are multiplied, added to the accumulators once they have landed, and
-// the result is stored from the registers: HBM reads overlap the product and nothing is staged in LDS.
-// Vector-memory operations complete in issue order, so "slab s landed" is a count of the operations issued after
-// that slab's four loads; every lane issues every load (addresses are clamped into the workspace, never skipped)
-// to keep that count the same for all wavefronts.
-#define KFAC_VM_WAIT_BARRIER(n) asm volatile("s_waitcnt vmcnt(" #n ")\n\ts_barrier" ::: "memory")
-
-__device__ __forceinline__ void upd_regular_mid(const UpdCtx& c, const gfloat* __restrict__ U, float* __restrict__ lds) {
-    typedef __attribute__((address_space(3))) unsigned char lds_byte;
-    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int lm = lane & 31, h = lane >> 5;
-    const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
-    lds_byte* l0 = (lds_byte*)lds;
-
-    // ---- producer: wavefronts 0,1 stream T_I, wavefronts 2,3 stream U_J; four 1 KB blocks each per stage ----
-    const int pan = wave >> 1;
-    const int drow = lane >> 2, dchunk = (lane & 3) ^ ((lane >> 3) & 3);
-    const gfloat* src0 = (pan == 0 ? c.T + (size_t)c.i0 * NB : U + (size_t)c.j0 * NB) + (size_t)drow * NB + 4 * dchunk;
-    auto issue = [&](int s, int buf) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int b = (wave & 1) + 2 * j;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src0 + (size_t)(16 * b) * NB + s * UK),
-                                             (__attribute__((address_space(3))) void*)(l0 + buf * USTAGE + pan * UPANEL + b * 1024),
-                                             16, 0, 0);
-        }
-    };
-
-    // ---- consumer: per-lane LDS byte addresses of the float4 holding k = 8 s2 + 4 h .. +3 of its row ----
-    unsigned a_addr[2][2], b_addr[2][2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const int ma = wm * 64 + q * 32 + lm, mb_ = wn * 64 + q * 32 + lm;
-            const int ch = 2 * s2 + h;
-            a_addr[q][s2] = (unsigned)((ma >> 4) * 1024 + (4 * (ma & 15) + (ch ^ (((ma & 15) >> 1) & 3))) * 16);
-            b_addr[q][s2] = (unsigned)(UPANEL + (mb_ >> 4) * 1024 + (4 * (mb_ & 15) + (ch ^ (((mb_ & 15) >> 1) & 3))) * 16);
-        }
-
-    // ---- the tile in the working copy: uniform base + per-lane byte offset (one per 32-column block) ----
-    // Rows up to the padded dimension exist in the workspace, so only columns need clamping for the loads.
-    gfloat* wtile = c.W + (size_t)c.i0 * c.ldw + c.j0;
-    const unsigned long long wt = (unsigned long long)wtile;                       // uniform: keep it in scalar registers
-    // (readfirstlane returns int: go through unsigned, or a low word with bit 31 set would sign-extend into the high word)
-    const unsigned wt_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)wt);
-    const unsigned wt_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(wt >> 32));
-    const unsigned long long wts = ((unsigned long long)wt_hi << 32) | (unsigned long long)wt_lo;
-    const unsigned row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(c.ldw) * 4u;
-    bool colok[2];
-    unsigned voff[2];
-#pragma unroll
-    for (int nbk = 0; nbk < 2; ++nbk) {
-        colok[nbk] = c.j0 + wn * 64 + nbk * 32 < c.ldw;
-        const int col = colok[nbk] ? wn * 64 + nbk * 32 + lm : lm;
-        voff[nbk] = (unsigned)(((wm * 64 + 4 * h) * c.ldw + col) * 4);
-    }
-    const int rows_left = c.irows - wm * 64 - 4 * h;      // tile rows from the lane's first row on
-
-    float old[2][16];
-    auto load_old = [&](int mb, int nbk) {                // 16 loads
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const unsigned long long base = wts + (unsigned long long)(mb * 32 + (r >> 2) * 8 + (r & 3)) * row_bytes;
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(old[nbk][r]) : "v"(voff[nbk]), "s"(base) : "memory");
-        }
-    };
-    auto landed = [&]() {                                 // orders every later use of old[][] after the wait before it
-#pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
-            asm volatile("" : "+v"(old[nbk][0]), "+v"(old[nbk][1]), "+v"(old[nbk][2]), "+v"(old[nbk][3]), "+v"(old[nbk][4]),
-                         "+v"(old[nbk][5]), "+v"(old[nbk][6]), "+v"(old[nbk][7]), "+v"(old[nbk][8]), "+v"(old[nbk][9]),
-                         "+v"(old[nbk][10]), "+v"(old[nbk][11]), "+v"(old[nbk][12]), "+v"(old[nbk][13]), "+v"(old[nbk][14]),
-                         "+v"(old[nbk][15]));
-    };
-
-    TileAcc acc;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = 0.f;
-
-    TR(1);
-    issue(0, 0);
-    issue(1, 1);
-    // Issue order per slab s: [slab s+2's four loads] [16 old-value loads in slabs 0, 1, 4, 5].
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        // operations that may still be in flight once slab s has landed
-        if (s == 0) KFAC_VM_WAIT_BARRIER(4);              // slab 1
-        else if (s == 1) KFAC_VM_WAIT_BARRIER(20);        // slab 2, old (0,0)
-        else if (s == 2) KFAC_VM_WAIT_BARRIER(36);        // old (0,0), slab 3, old (0,1)
-        else if (s == 3) KFAC_VM_WAIT_BARRIER(20);        // old (0,1), slab 4
-        else if (s == 4) KFAC_VM_WAIT_BARRIER(4);         // slab 5: the first half of the old values is in
-        else if (s == 5) KFAC_VM_WAIT_BARRIER(20);        // slab 6, old (1,0)
-        else if (s == 6) KFAC_VM_WAIT_BARRIER(36);        // old (1,0), slab 7, old (1,1)
-        else KFAC_VM_WAIT_BARRIER(16);                    // old (1,1)
-        if (s == 0) TR(2);
-        if (s + 2 < 8) issue(s + 2, (s + 2) % UNS);       // refill the slot slab s-1 vacated
-        if (s == 4) {
-            landed();
-#pragma unroll
-            for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc.c[0][nbk][r] += old[nbk][r];
-        }
-        if (s == 0 || s == 1) load_old(0, s);
-        if (s == 4 || s == 5) load_old(1, s - 4);
-        if (!dead) {
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                v4f a[2], bb[2];
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    KFAC_LDS_READ128(a[q], a_addr[q][s2], (s % UNS) * USTAGE);
-                    KFAC_LDS_READ128(bb[q], b_addr[q][s2], (s % UNS) * USTAGE);
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(bb[0]), "+v"(bb[1]));
-                a[0] = -a[0]; a[1] = -a[1];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                        for (int nbk = 0; nbk < 2; ++nbk)
-                            acc.c[mb][nbk] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb][i], bb[nbk][i], acc.c[mb][nbk], 0, 0, 0);
-            }
-        }
-    }
-    TR(3);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    landed();
-    TR(4);
-    if (dead) return;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
-                const float v = acc.c[mb][nbk][r] + (mb == 1 ? old[nbk][r] : 0.f);
-                if (colok[nbk] && dr < rows_left)
-                    *(gfloat*)((KFAC_AS1 char*)(wtile + (size_t)dr * c.ldw) + voff[nbk]) = v;
-            }
-    TR(5);
-}
-
-// Same tile, product on the bf16 matrix cores with both operands split three ways (gemm_split.h): the accumulators
-// start as the tile's old values (fetched straight into MFMA register layout), the negated product is added, and
-// the result is stored from the registers.
+// full (K = 128).  The product runs on the bf16 matrix cores with both operands split three ways (gemm_split.h):
+// the accumulators start as the tile's old values (fetched straight into MFMA register layout: register r of a
+// 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated product is added, and the result is
+// stored from the registers: nothing is staged in LDS.
 __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfloat* __restrict__ U, unsigned char* __restrict__ lds) {
     [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
@@ -909,8 +752,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     c.diag = I == J;
     if (I != kb && J != kb) {
         if (last) upd_regular<true>(c, ws.U, lds);
-        else if (UPD_SPLIT) upd_regular_mid_split(c, ws.U, (unsigned char*)lds);
-        else upd_regular_mid(c, ws.U, lds);
+        else upd_regular_mid_split(c, ws.U, (unsigned char*)lds);
     } else if (last) {
         upd_panel<true>(c, J == kb, lds);
     } else {

@@ -128,6 +128,37 @@ def factor_bytes(layers, bytes_per_el: int = 4) -> int:
     return sum((l.d_A ** 2 + l.d_G ** 2) * bytes_per_el for l in layers)
 
 
+def pack_upper(S) -> np.ndarray:
+    """Upper triangle of a symmetric n x n matrix, row by row: row i contributes S[i, i], S[i, i+1], ..., S[i, n-1]
+    (Sec. 3.4, symmetry-aware communication: only the upper triangular part of a factor is sent)."""
+    S = np.asarray(S, dtype=np.float64)
+    n = S.shape[0]
+    out = []
+    for i in range(n):
+        out.append(S[i, i:])
+    return np.concatenate(out) if out else np.zeros(0)
+
+
+def unpack_upper(packed, n: int) -> np.ndarray:
+    """The symmetric n x n matrix whose upper triangle, row by row, is `packed` (inverse of pack_upper)."""
+    packed = np.asarray(packed, dtype=np.float64)
+    S = np.zeros((n, n))
+    pos = 0
+    for i in range(n):
+        row = packed[pos:pos + n - i]
+        S[i, i:] = row
+        S[i:, i] = row
+        pos += n - i
+    return S
+
+
+def ema_packed(running, packed_fresh, decay: float) -> np.ndarray:
+    """Running average of a full symmetric factor from a fresh factor that arrives as a packed upper triangle (what a
+    layer's owner does with the reduced, packed statistics: Sec. 3.3 stage 3 -> 4 with the packing of Sec. 3.4)."""
+    running = np.asarray(running, dtype=np.float64)
+    return ema(running, unpack_upper(packed_fresh, running.shape[0]), decay)
+
+
 def packed_triangle_elems(n: int) -> int:
     """Entries of the upper triangle of an n x n symmetric matrix (Sec. 3.4, symmetry-aware communication)."""
     return n * (n + 1) // 2

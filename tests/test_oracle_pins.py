@@ -350,3 +350,34 @@ def test_bf16_rounding_helper():
     want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(got, want)
     assert synth.bf16_bits(got).dtype == np.uint16
+
+
+# ---------------------------------------------------------------------------------------------------
+# packed upper triangles (Sec. 3.4, symmetry-aware communication)
+# ---------------------------------------------------------------------------------------------------
+def test_pack_upper_matches_library_triangle_indexing_and_counts():
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 5, 33):
+        B = rng.standard_normal((n, n))
+        S = B + B.T
+        p = ko.pack_upper(S)
+        assert p.shape == (ko.packed_triangle_elems(n),) == (n * (n + 1) // 2,)
+        np.testing.assert_array_equal(p, S[np.triu_indices(n)])            # numpy's own row-major upper-triangle order
+        np.testing.assert_array_equal(ko.unpack_upper(p, n), S)             # round trip rebuilds both triangles
+    # hand-written 3 x 3: rows (1 2 3), (. 4 5), (. . 6)
+    S3 = np.array([[1., 2., 3.], [2., 4., 5.], [3., 5., 6.]])
+    np.testing.assert_array_equal(ko.pack_upper(S3), [1., 2., 3., 4., 5., 6.])
+    np.testing.assert_array_equal(ko.unpack_upper([1., 2., 3., 4., 5., 6.], 3), S3)
+
+
+def test_pack_upper_reads_only_the_upper_triangle():
+    S = np.array([[1., 2.], [99., 4.]])                                     # lower entry must not leak into the result
+    np.testing.assert_array_equal(ko.pack_upper(S), [1., 2., 4.])
+
+
+def test_ema_packed_equals_ema_of_the_full_matrix():
+    rng = np.random.default_rng(6)
+    n = 7
+    B = rng.standard_normal((n, n)); X = B @ B.T
+    R = np.eye(n)
+    np.testing.assert_allclose(ko.ema_packed(R, X[np.triu_indices(n)], 0.95), 0.95 * R + 0.05 * X, rtol=0, atol=1e-15)

@@ -106,6 +106,33 @@ def stage_times(net, reps=3):
     return acc
 
 
+def packed_triangle_rates(net, reps=5):
+    """Outside the step: packing all 108 running factors into upper triangles and feeding the running averages from
+    packed factors (the sender's and the owner's side of the symmetry-aware exchange), as HBM rates."""
+    full = [t for l in net.layers for t in (l.A_new, l.G_new)]
+    run = [t.clone() for l in net.layers for t in (l.A_run, l.G_run)]
+    packed = [torch.empty(kb.packed_elems(t.shape[0]), device=t.device) for t in full]
+    pack_batch, ema_batch = kb.PackBatch(full, packed), kb.PackBatch(run, packed)
+    dims = [int(t.shape[0]) for t in full]
+    res = {}
+    for name, fn, nbytes in (
+            ("pack_upper_batched", lambda: kb.kfac_pack_upper_batched(pack_batch), sum(4.0 * d * (d + 1) for d in dims)),
+            ("ema_packed_batched", lambda: kb.kfac_ema_packed_batched(ema_batch, 0.95),
+             sum(4.0 * d * (d + 1) + 4.0 * d * d for d in dims))):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rate = nbytes / (ms * 1e-3) / 1e9
+        res[name] = {"ms": round(ms, 4), "bound": "hbm", "achieved": round(rate, 1), "peak": PEAK["hbm"], "unit": "GB/s",
+                     "frac": round(rate / PEAK["hbm"], 4)}
+    return res
+
+
 def cpu_oracle_baseline(net, sample_names):
     """The float64 oracle, as it stands, on a few layers of the same workload; scaled to a whole step by
     algorithmic flops.  Reported baseline only."""
@@ -221,6 +248,7 @@ def main():
         "roofline": roofline,
         "kernels": per_kernel,
     }
+    out["next_rows"] = packed_triangle_rates(net)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_oracle_baseline(
             net, {"conv1", "layer1.0.conv2", "layer2.1.conv1", "layer3.1.conv2", "layer3.2.conv2", "layer4.0.conv2",

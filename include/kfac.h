@@ -114,6 +114,29 @@ typedef struct kfac_ema_item {
 
 int kfac_ema_batched(const kfac_ema_item* items_host, int32_t count, float decay, void* stream);
 
+/* Packed upper triangles (Sec. 3.4, symmetry-aware communication: a symmetric factor travels as its upper triangle).
+ * Packed layout: row i contributes full[i][i], full[i][i+1], ..., full[i][dim-1], rows in order: dim (dim + 1) / 2
+ * floats.  Only the upper triangle of `full` is read.  One launch per 128 matrices.  The arrays are read on the host
+ * during the call; every pointer in them is a device pointer; full and packed must not overlap. */
+typedef struct kfac_pack_item {
+    const float* full;   /* dim x dim, row-major */
+    float* packed;       /* dim (dim + 1) / 2 */
+    int32_t dim;
+} kfac_pack_item;
+
+int kfac_pack_upper_batched(const kfac_pack_item* items_host, int32_t count, void* stream);
+
+/* running[dim x dim] <- decay * running + (1 - decay) * X, where the fresh symmetric factor X arrives packed (what a
+ * layer's owner holds after the reduction of Algorithm 1 stage 3 when factors are sent packed).  Both triangles of
+ * `running` are written (the lower one as the mirror image of the upper one); only its upper triangle is read. */
+typedef struct kfac_ema_packed_item {
+    float* running;            /* dim x dim, updated in place */
+    const float* packed_fresh; /* dim (dim + 1) / 2 */
+    int32_t dim;
+} kfac_ema_packed_item;
+
+int kfac_ema_packed_batched(const kfac_ema_packed_item* items_host, int32_t count, float decay, void* stream);
+
 /* Workspace for kfac_damped_inverse of one dim x dim matrix. */
 size_t kfac_inverse_workspace_bytes(int32_t dim);
 

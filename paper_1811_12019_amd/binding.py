@@ -27,7 +27,7 @@ KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 
 EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
-    "kfac_ema", "kfac_ema_batched",
+    "kfac_ema", "kfac_ema_batched", "kfac_pack_upper_batched", "kfac_ema_packed_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -46,6 +46,14 @@ class kfac_factor_item(ctypes.Structure):
 
 class kfac_ema_item(ctypes.Structure):
     _fields_ = [("running", ctypes.c_void_p), ("fresh", ctypes.c_void_p), ("dim", ctypes.c_int32)]
+
+
+class kfac_pack_item(ctypes.Structure):
+    _fields_ = [("full", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("dim", ctypes.c_int32)]
+
+
+class kfac_ema_packed_item(ctypes.Structure):
+    _fields_ = [("running", ctypes.c_void_p), ("packed_fresh", ctypes.c_void_p), ("dim", ctypes.c_int32)]
 
 
 class kfac_inverse_item(ctypes.Structure):
@@ -94,6 +102,10 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_ema.argtypes = [vp, vp, i32, f32, vp]
     lib.kfac_ema_batched.restype = ctypes.c_int
     lib.kfac_ema_batched.argtypes = [ctypes.POINTER(kfac_ema_item), i32, f32, vp]
+    lib.kfac_pack_upper_batched.restype = ctypes.c_int
+    lib.kfac_pack_upper_batched.argtypes = [ctypes.POINTER(kfac_pack_item), i32, vp]
+    lib.kfac_ema_packed_batched.restype = ctypes.c_int
+    lib.kfac_ema_packed_batched.argtypes = [ctypes.POINTER(kfac_ema_packed_item), i32, f32, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
@@ -226,6 +238,37 @@ class EmaBatch:
 def kfac_ema_batched(batch: EmaBatch, decay: float, stream=None) -> None:
     rc = load_library().kfac_ema_batched(batch.host, batch.count, float(decay), _stream(stream))
     _check(rc, "kfac_ema_batched")
+
+
+def packed_elems(dim: int) -> int:
+    return dim * (dim + 1) // 2
+
+
+class PackBatch:
+    """kfac_pack_item / kfac_ema_packed_item tables (host memory) over the same (full, packed) tensor pairs."""
+
+    def __init__(self, full: Sequence[torch.Tensor], packed: Sequence[torch.Tensor]):
+        n = len(full)
+        self.count = n
+        self.keep = (list(full), list(packed))
+        self.pack_items = (kfac_pack_item * max(n, 1))()
+        self.ema_items = (kfac_ema_packed_item * max(n, 1))()
+        for i in range(n):
+            d = int(full[i].shape[0])
+            assert packed[i].numel() == packed_elems(d)
+            self.pack_items[i] = kfac_pack_item(full[i].data_ptr(), packed[i].data_ptr(), d)
+            self.ema_items[i] = kfac_ema_packed_item(full[i].data_ptr(), packed[i].data_ptr(), d)
+
+
+def kfac_pack_upper_batched(batch: PackBatch, stream=None) -> None:
+    """packed[i] <- upper triangle of full[i]."""
+    _check(load_library().kfac_pack_upper_batched(batch.pack_items, batch.count, _stream(stream)), "kfac_pack_upper_batched")
+
+
+def kfac_ema_packed_batched(batch: PackBatch, decay: float, stream=None) -> None:
+    """full[i] (a running average) <- decay * full[i] + (1 - decay) * unpack(packed[i])."""
+    _check(load_library().kfac_ema_packed_batched(batch.ema_items, batch.count, float(decay), _stream(stream)),
+           "kfac_ema_packed_batched")
 
 
 def kfac_inverse_workspace_bytes(dim: int) -> int:

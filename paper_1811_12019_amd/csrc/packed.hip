@@ -1,0 +1,198 @@
+// Packed upper triangles of the symmetric Kronecker factors (Sec. 3.4, symmetry-aware communication: only the upper
+// triangular part of a factor travels), and the running average fed from a packed factor.
+//
+// Packed layout: row i of the upper triangle contributes S[i][i], S[i][i+1], ..., S[i][n-1], rows in order; row i
+// starts at i n - i (i - 1) / 2 and the whole has n (n + 1) / 2 elements.
+// Both kernels work on 64 x 64 tiles (I <= J) of the matrix, one workgroup per tile, all matrices of a call in one
+// launch (workgroup -> matrix through prefix sums in the kernel arguments): a tile row is a contiguous run both in
+// the full matrix and in the packed array, and the mirrored tile of the running average is written row-wise after a
+// transpose through LDS.  HBM bound.
+#include "common.h"
+
+namespace kfac {
+
+constexpr int PK_T = 64;              // tile edge
+constexpr int PK_MAX = 128;           // matrices per launch (keeps the argument block under 4 KB)
+
+struct PackBatch {
+    int count;
+    unsigned prefix[PK_MAX + 1];      // first workgroup of matrix i
+    int dim[PK_MAX];
+    float* full[PK_MAX];              // dim x dim
+    float* packed[PK_MAX];            // dim (dim + 1) / 2
+};
+
+static inline __host__ __device__ int pk_tiles(int dim) { const int t = (dim + PK_T - 1) / PK_T; return t * (t + 1) / 2; }
+
+__device__ __forceinline__ size_t pk_row_start(int i, int n) { return (size_t)i * n - (size_t)i * (i - 1) / 2; }
+
+__device__ __forceinline__ void pk_locate(const PackBatch& b, int& m, int& I, int& J) {
+    const unsigned wg = blockIdx.x;
+    const int t = threadIdx.x;
+    m = __syncthreads_count(t < b.count - 1 && b.prefix[t + 1] <= wg);     // matrices that end before this workgroup
+    // consecutive workgroups walk along a tile row (neighbouring tiles are neighbours in memory, in the full matrix
+    // and in the packed array): pairs (a >= b) with b fastest, read as (tile row, tile column) = (T-1-a, T-1-b)
+    int a, bb;
+    tri_decode((int)(wg - b.prefix[m]), a, bb);
+    const int T = (b.dim[m] + PK_T - 1) / PK_T;
+    I = T - 1 - a; J = T - 1 - bb;                                           // tile row <= tile column
+}
+
+// Thread = 4 consecutive columns of one tile row (16-byte accesses at 4-byte alignment: rows of an odd-sized matrix
+// and rows of the packed array start anywhere); 16 tile rows per pass, 4 passes.
+__device__ __forceinline__ v4f pk_load4(const gfloat* p, int valid_from, int valid_to) {     // elements [from, to) of 4
+    if (valid_from == 0 && valid_to == 4) return *(const KFAC_AS1 v4f_a4*)p;
+    v4f v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (e >= valid_from && e < valid_to) v[e] = p[e];
+    return v;
+}
+
+__device__ __forceinline__ void pk_store4(gfloat* p, const v4f& v, int valid_from, int valid_to) {
+    if (valid_from == 0 && valid_to == 4) { *(KFAC_AS1 v4f_a4*)p = v; return; }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (e >= valid_from && e < valid_to) p[e] = v[e];
+}
+
+// packed <- upper triangle of full
+__global__ __launch_bounds__(256) void pack_upper_kernel(PackBatch b) {
+    int m, I, J;
+    pk_locate(b, m, I, J);
+    const int n = b.dim[m];
+    const gfloat* __restrict__ S = as_global(b.full[m]);
+    gfloat* __restrict__ P = as_global(b.packed[m]);
+    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+    const int j = J * PK_T + c4;
+    v4f v[4];
+    int from[4], to[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int i = I * PK_T + r0 + 16 * p;
+        from[p] = min(4, max(0, i - j));              // columns left of the diagonal are not part of the triangle
+        to[p] = i < n ? min(4, max(0, n - j)) : 0;
+        if (from[p] >= to[p]) { from[p] = to[p] = 0; continue; }
+        v[p] = pk_load4(S + (size_t)i * n + j, from[p], to[p]);
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int i = I * PK_T + r0 + 16 * p;
+        if (from[p] < to[p]) pk_store4(P + pk_row_start(i, n) + (j - i), v[p], from[p], to[p]);
+    }
+}
+
+// running <- decay * running + (1 - decay) * unpack(packed), both triangles of running written, exactly symmetric
+__global__ __launch_bounds__(256) void ema_packed_kernel(PackBatch b, float decay, float one_minus) {
+    __shared__ float tile[PK_T][PK_T + 1];
+    int m, I, J;
+    pk_locate(b, m, I, J);
+    const int n = b.dim[m];
+    gfloat* __restrict__ R = as_global(b.full[m]);
+    const gfloat* __restrict__ P = as_global(b.packed[m]);
+    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+    const int j = J * PK_T + c4;
+    v4f run[4], fresh[4];
+    int from[4], to[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int i = I * PK_T + r0 + 16 * p;
+        from[p] = min(4, max(0, i - j));
+        to[p] = i < n ? min(4, max(0, n - j)) : 0;
+        if (from[p] >= to[p]) { from[p] = to[p] = 0; continue; }
+        run[p] = pk_load4(R + (size_t)i * n + j, from[p], to[p]);
+        fresh[p] = pk_load4(P + pk_row_start(i, n) + (j - i), from[p], to[p]);
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = r0 + 16 * p, i = I * PK_T + r;
+        v4f v = {0.f, 0.f, 0.f, 0.f};
+        if (from[p] < to[p]) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = fmaf(decay, run[p][e], one_minus * fresh[p][e]);
+            pk_store4(R + (size_t)i * n + j, v, from[p], to[p]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[r][c4 + e] = v[e];
+    }
+    __syncthreads();
+    // mirror image: row J*64 + r', columns I*64 + c' <- tile[c'][r'], strictly below the diagonal only
+    const int i2 = I * PK_T + c4;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = r0 + 16 * p, j2 = J * PK_T + r;
+        if (j2 >= n) continue;
+        const int hi = min(4, min(n - i2, j2 - i2));             // columns i2 + e < min(n, j2)
+        if (hi <= 0) continue;
+        v4f v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = tile[c4 + e][r];
+        pk_store4(R + (size_t)j2 * n + i2, v, 0, hi);
+    }
+}
+
+static int fill_pack(PackBatch& b, const int* dims, float* const* full, float* const* packed, int cnt) {
+    b.count = cnt;
+    unsigned wgs = 0;
+    for (int i = 0; i < cnt; ++i) {
+        b.prefix[i] = wgs;
+        b.dim[i] = dims[i];
+        b.full[i] = full[i];
+        b.packed[i] = packed[i];
+        wgs += (unsigned)pk_tiles(dims[i]);
+    }
+    b.prefix[cnt] = wgs;
+    return (int)wgs;
+}
+
+}  // namespace kfac
+
+using namespace kfac;
+
+static bool tri_args_ok(const void* full, const void* packed, int dim) {
+    if (!full || !packed || dim <= 0 || dim > 32768) return false;
+    const size_t nf = (size_t)dim * dim * sizeof(float), np = (size_t)dim * (dim + 1) / 2 * sizeof(float);
+    const char *f = (const char*)full, *p = (const char*)packed;
+    return f + nf <= p || p + np <= f;                                       // no overlap
+}
+
+extern "C" int kfac_pack_upper_batched(const kfac_pack_item* items_host, int32_t count, void* stream) {
+    if (!items_host || count < 0) return KFAC_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        if (!tri_args_ok(items_host[i].full, items_host[i].packed, items_host[i].dim)) return KFAC_ERR_INVALID_ARG;
+    for (int first = 0; first < count; first += PK_MAX) {
+        const int cnt = count - first < PK_MAX ? count - first : PK_MAX;
+        int dims[PK_MAX];
+        float *full[PK_MAX], *packed[PK_MAX];
+        for (int i = 0; i < cnt; ++i) {
+            dims[i] = items_host[first + i].dim;
+            full[i] = const_cast<float*>(items_host[first + i].full);
+            packed[i] = items_host[first + i].packed;
+        }
+        PackBatch b;
+        const int wgs = fill_pack(b, dims, full, packed, cnt);
+        KFAC_LAUNCH(pack_upper_kernel, dim3(wgs), dim3(256), (hipStream_t)stream, b);
+    }
+    return KFAC_OK;
+}
+
+extern "C" int kfac_ema_packed_batched(const kfac_ema_packed_item* items_host, int32_t count, float decay, void* stream) {
+    if (!items_host || count < 0) return KFAC_ERR_INVALID_ARG;
+    if (!(decay >= 0.f && decay <= 1.f)) return KFAC_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        if (!tri_args_ok(items_host[i].running, items_host[i].packed_fresh, items_host[i].dim)) return KFAC_ERR_INVALID_ARG;
+    for (int first = 0; first < count; first += PK_MAX) {
+        const int cnt = count - first < PK_MAX ? count - first : PK_MAX;
+        int dims[PK_MAX];
+        float *full[PK_MAX], *packed[PK_MAX];
+        for (int i = 0; i < cnt; ++i) {
+            dims[i] = items_host[first + i].dim;
+            full[i] = items_host[first + i].running;
+            packed[i] = const_cast<float*>(items_host[first + i].packed_fresh);
+        }
+        PackBatch b;
+        const int wgs = fill_pack(b, dims, full, packed, cnt);
+        KFAC_LAUNCH(ema_packed_kernel, dim3(wgs), dim3(256), (hipStream_t)stream, b, decay, 1.0f - decay);
+    }
+    return KFAC_OK;
+}

@@ -88,6 +88,17 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_ema_batched(None, 1, 0.95, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_ema_batched(items, 1, -0.1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_ema_batched(items, 0, 0.95, None) == kb.KFAC_OK                     # nothing to do, no launch
+    pk = (kb.kfac_pack_item * 1)(kb.kfac_pack_item(0x10000, 0x10010, 4))                 # packed inside full
+    assert lib.kfac_pack_upper_batched(pk, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    pk[0] = kb.kfac_pack_item(0x10000, 0x90000, 0)
+    assert lib.kfac_pack_upper_batched(pk, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_pack_upper_batched(None, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_pack_upper_batched(pk, 0, None) == kb.KFAC_OK
+    ep = (kb.kfac_ema_packed_item * 1)(kb.kfac_ema_packed_item(0x10000, 0x90000, 4))
+    assert lib.kfac_ema_packed_batched(ep, 1, 1.5, None) == kb.KFAC_ERR_INVALID_ARG
+    ep[0] = kb.kfac_ema_packed_item(0x10000, None, 4)
+    assert lib.kfac_ema_packed_batched(ep, 1, 0.95, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_ema_packed_batched(ep, 0, 0.95, None) == kb.KFAC_OK
 
     assert lib.kfac_damped_inverse(fake, 0, 0.1, ctypes.c_void_p(0x9000), None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse(fake, 8, 0.1, fake, None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG   # in place

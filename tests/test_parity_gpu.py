@@ -245,6 +245,63 @@ def test_ema_batched_mixed_sizes():
 
 
 # ----------------------------------------------------------------------------------------------
+# packed upper triangles and the running average fed from a packed factor
+# ----------------------------------------------------------------------------------------------
+PACK_DIMS = [1, 2, 63, 64, 65, 128, 130, 577, 1025] + [3 + (i % 5) for i in range(125)]     # > 128 matrices: two launches
+
+
+def test_pack_upper_batched_bit_exact():
+    rng = np.random.default_rng(21)
+    full = [rng.standard_normal((d, d)).astype(np.float32) for d in PACK_DIMS]          # not symmetric on purpose:
+    ft = [torch.from_numpy(a).to(DEV) for a in full]                                    # only the upper triangle is read
+    pt = [torch.full((kb.packed_elems(d),), float("nan"), device=DEV) for d in PACK_DIMS]
+    kb.kfac_pack_upper_batched(kb.PackBatch(ft, pt))
+    torch.cuda.synchronize()
+    for a, p, f in zip(full, pt, ft):
+        np.testing.assert_array_equal(p.cpu().numpy(), ko.pack_upper(a).astype(np.float32))    # copies: bit exact
+        np.testing.assert_array_equal(f.cpu().numpy(), a)                                      # source untouched
+    kb.kfac_pack_upper_batched(kb.PackBatch([], []))                                           # empty batch
+
+
+def test_ema_packed_batched():
+    rng = np.random.default_rng(22)
+    run, packed = [], []
+    for d in PACK_DIMS:
+        B = rng.standard_normal((d, d)).astype(np.float32)
+        run.append((B + B.T).astype(np.float32))
+        C = rng.standard_normal((d, d)).astype(np.float32)
+        packed.append(ko.pack_upper(C + C.T).astype(np.float32))
+    rt = [torch.from_numpy(a.copy()).to(DEV) for a in run]
+    for r in rt:                                                     # poison the lower triangles: they must not be read
+        r.copy_(torch.triu(r) + torch.tril(torch.full_like(r, 1e30), diagonal=-1))
+    pk = [torch.from_numpy(a).to(DEV) for a in packed]
+    kb.kfac_ema_packed_batched(kb.PackBatch(rt, pk), 0.95)
+    torch.cuda.synchronize()
+    for a, p, r in zip(run, packed, rt):
+        want = ko.ema_packed(a, p, np.float32(0.95))
+        got = r.cpu().numpy()
+        np.testing.assert_allclose(got, want, rtol=0, atol=2e-7 * max(np.abs(want).max(), 1.0))
+        np.testing.assert_array_equal(got, got.T)                   # mirrored, not recomputed
+
+
+def test_pack_then_ema_packed_equals_plain_ema():
+    """pack on the sender, running average from the packed factor on the owner = running average of the full factor."""
+    d = 300
+    rng = np.random.default_rng(23)
+    B = rng.standard_normal((d, d)).astype(np.float32)
+    X = (B @ B.T / d).astype(np.float32)
+    X = np.triu(X) + np.triu(X, 1).T
+    Xt = torch.from_numpy(X).to(DEV)
+    pk = torch.empty(kb.packed_elems(d), device=DEV)
+    kb.kfac_pack_upper_batched(kb.PackBatch([Xt], [pk]))
+    R1, R2 = torch.eye(d, device=DEV), torch.eye(d, device=DEV)
+    kb.kfac_ema_packed_batched(kb.PackBatch([R1], [pk]), 0.95)
+    kb.kfac_ema(R2, Xt, d, 0.95)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(R1.cpu().numpy(), R2.cpu().numpy())
+
+
+# ----------------------------------------------------------------------------------------------
 # damped inverse
 # ----------------------------------------------------------------------------------------------
 def gpu_inverse(S, damping):

@@ -443,7 +443,7 @@ static int run_factor_items(const kfac_factor_item* host, const kfac_factor_item
                 if ((plain ? 0 : 2) + (f16 ? 1 : 0) != variant) continue;
                 const FactorPlan p = plan_dma(u, target);
                 b.index[b.count] = next;
-                b.prefix[b.count + 1] = b.prefix[b.count] + p.ntiles * p.nsplit;
+                b.prefix[b.count + 1] = b.prefix[b.count] + align_up(p.ntiles * p.nsplit, 8);   // see factor_dma_tile
                 if (!dev) b.single = host[next];
                 ++b.count;
                 if (p.nsplit > 1) {

@@ -69,17 +69,18 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
     const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, h = lane >> 5;
 
+    // The caller pads every build's workgroup count to a multiple of 8 and starts it at a multiple of 8, so that
+    // wg % 8 is the XCD this workgroup runs on (workgroups are dealt to the 8 XCDs round-robin).  XCD x takes the
+    // x-th contiguous eighth of the build's work list (row ranges in order, tiles row-major inside a range): the
+    // tiles of a row range, which all read the same rows, share one L2 instead of fetching them eight times.
     int split, tile;
     {
-        const int id = wg;
-        if ((nsplit & 7) == 0) {          // same row range -> same XCD (ids equal mod 8)
-            const int xcd = id & 7, j = id >> 3;
-            split = xcd + 8 * (j / ntiles);
-            tile = j % ntiles;
-        } else {
-            split = id / ntiles;
-            tile = id - split * ntiles;
-        }
+        const int work = ntiles * nsplit;
+        const int per_xcd = (work + 7) >> 3;
+        const int unit = (wg & 7) * per_xcd + (wg >> 3);
+        if ((wg >> 3) >= per_xcd || unit >= work) return;      // padding workgroup (uniform, before any barrier)
+        split = unit / ntiles;
+        tile = unit - split * ntiles;
     }
     int I, J;
     tri_decode(tile, I, J);

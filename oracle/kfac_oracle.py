@@ -159,6 +159,30 @@ def ema_packed(running, packed_fresh, decay: float) -> np.ndarray:
     return ema(running, unpack_upper(packed_fresh, running.shape[0]), decay)
 
 
+def factor_diff(X, X_prev) -> float:
+    """Change rate of a statistic between two refreshes, ||X - X_prev||_F / ||X_prev||_F (Sec. 5.4, "Staleness of
+    Fisher information")."""
+    X = np.asarray(X, dtype=np.float64)
+    X_prev = np.asarray(X_prev, dtype=np.float64)
+    num = 0.0
+    den = 0.0
+    for a, b in zip(X.ravel(), X_prev.ravel()):
+        num += (a - b) * (a - b)
+        den += b * b
+    return float(np.sqrt(num) / np.sqrt(den))
+
+
+def refresh_interval(epoch: int) -> int:
+    """Iterations between refreshes of the statistics in epoch e: min(20, 5 * floor(e / 5) + 1) (Sec. 5.4, "Training with
+    stale Fisher information", first heuristic)."""
+    return min(20, 5 * (int(epoch) // 5) + 1)
+
+
+def refresh_interval_late(epoch: int) -> int:
+    """The second heuristic of Sec. 5.4: every iteration before epoch 13, every 20th from then on."""
+    return 1 if int(epoch) < 13 else 20
+
+
 def packed_triangle_elems(n: int) -> int:
     """Entries of the upper triangle of an n x n symmetric matrix (Sec. 3.4, symmetry-aware communication)."""
     return n * (n + 1) // 2

@@ -381,3 +381,27 @@ def test_ema_packed_equals_ema_of_the_full_matrix():
     B = rng.standard_normal((n, n)); X = B @ B.T
     R = np.eye(n)
     np.testing.assert_allclose(ko.ema_packed(R, X[np.triu_indices(n)], 0.95), 0.95 * R + 0.05 * X, rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------------------------------
+# staleness: change rate and refresh intervals (Sec. 5.4)
+# ---------------------------------------------------------------------------------------------------
+def test_factor_diff_closed_forms():
+    rng = np.random.default_rng(8)
+    P = rng.standard_normal((6, 6))
+    assert ko.factor_diff(P, P) == 0.0
+    assert ko.factor_diff(2.0 * P, P) == pytest.approx(1.0, rel=1e-14)             # ||P|| / ||P||
+    assert ko.factor_diff(0.0 * P, P) == pytest.approx(1.0, rel=1e-14)
+    assert ko.factor_diff(3.0 * P, 3.0 * 0.5 * P) == pytest.approx(1.0, rel=1e-14)  # scale invariant
+    # 3-4-5: X_prev = (3, 0), X = (3, 4): ||X - X_prev|| = 4, ||X_prev|| = 3
+    assert ko.factor_diff(np.array([[3.0, 4.0]]), np.array([[3.0, 0.0]])) == pytest.approx(4.0 / 3.0, rel=1e-15)
+    # library norm as an independent routine; not symmetric in its arguments (the OLD value normalises)
+    Q = rng.standard_normal((6, 6))
+    assert ko.factor_diff(Q, P) == pytest.approx(np.linalg.norm(Q - P) / np.linalg.norm(P), rel=1e-13)
+    assert ko.factor_diff(Q, P) != pytest.approx(ko.factor_diff(P, Q), rel=1e-3)
+
+
+def test_refresh_intervals_worked_values():
+    # min(20, 5 floor(e/5) + 1): 1 for epochs 0-4, 6 for 5-9, 11 for 10-14, 16 for 15-19, capped at 20 from epoch 20 on
+    assert [ko.refresh_interval(e) for e in (0, 4, 5, 9, 10, 14, 15, 19, 20, 44)] == [1, 1, 6, 6, 11, 11, 16, 16, 20, 20]
+    assert [ko.refresh_interval_late(e) for e in (0, 12, 13, 44)] == [1, 1, 20, 20]

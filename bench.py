@@ -107,15 +107,18 @@ def stage_times(net, reps=3):
 
 
 def packed_triangle_rates(net, reps=5):
-    """Outside the step: packing all 108 running factors into upper triangles and feeding the running averages from
-    packed factors (the sender's and the owner's side of the symmetry-aware exchange), as HBM rates."""
+    """Outside the step: the change rate of all 108 factors between two refreshes, packing them into upper triangles, and
+    feeding the running averages from packed factors (the sender's and the owner's side of the symmetry-aware
+    exchange), as HBM rates."""
     full = [t for l in net.layers for t in (l.A_new, l.G_new)]
     run = [t.clone() for l in net.layers for t in (l.A_run, l.G_run)]
     packed = [torch.empty(kb.packed_elems(t.shape[0]), device=t.device) for t in full]
     pack_batch, ema_batch = kb.PackBatch(full, packed), kb.PackBatch(run, packed)
     dims = [int(t.shape[0]) for t in full]
+    diff_batch = kb.DiffBatch(full, run)
     res = {}
     for name, fn, nbytes in (
+            ("factor_diff_batched", lambda: kb.kfac_factor_diff_batched(diff_batch), sum(8.0 * d * d for d in dims)),
             ("pack_upper_batched", lambda: kb.kfac_pack_upper_batched(pack_batch), sum(4.0 * d * (d + 1) for d in dims)),
             ("ema_packed_batched", lambda: kb.kfac_ema_packed_batched(ema_batch, 0.95),
              sum(4.0 * d * (d + 1) + 4.0 * d * d for d in dims))):

@@ -137,6 +137,20 @@ typedef struct kfac_ema_packed_item {
 
 int kfac_ema_packed_batched(const kfac_ema_packed_item* items_host, int32_t count, float decay, void* stream);
 
+/* Change rate of a statistic between two refreshes, out[i] = ||x - x_prev||_F / ||x_prev||_F (Sec. 5.4, staleness of
+ * the Fisher information), for `count` matrices; out is a device array of `count` floats.  Deterministic (fixed
+ * summation order, double accumulation across threads).  ws: device scratch of kfac_factor_diff_workspace_bytes
+ * bytes, 256-byte aligned.  The item array is read on the host during the call. */
+typedef struct kfac_diff_item {
+    const float* x;       /* dim x dim, device */
+    const float* x_prev;  /* dim x dim, device */
+    int32_t dim;
+} kfac_diff_item;
+
+size_t kfac_factor_diff_workspace_bytes(const kfac_diff_item* items_host, int32_t count);
+int kfac_factor_diff_batched(const kfac_diff_item* items_host, int32_t count, float* out, void* ws, size_t ws_bytes,
+                             void* stream);
+
 /* Workspace for kfac_damped_inverse of one dim x dim matrix. */
 size_t kfac_inverse_workspace_bytes(int32_t dim);
 

@@ -28,6 +28,7 @@ KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
     "kfac_ema", "kfac_ema_batched", "kfac_pack_upper_batched", "kfac_ema_packed_batched",
+    "kfac_factor_diff_workspace_bytes", "kfac_factor_diff_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -54,6 +55,10 @@ class kfac_pack_item(ctypes.Structure):
 
 class kfac_ema_packed_item(ctypes.Structure):
     _fields_ = [("running", ctypes.c_void_p), ("packed_fresh", ctypes.c_void_p), ("dim", ctypes.c_int32)]
+
+
+class kfac_diff_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("x_prev", ctypes.c_void_p), ("dim", ctypes.c_int32)]
 
 
 class kfac_inverse_item(ctypes.Structure):
@@ -106,6 +111,10 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_pack_upper_batched.argtypes = [ctypes.POINTER(kfac_pack_item), i32, vp]
     lib.kfac_ema_packed_batched.restype = ctypes.c_int
     lib.kfac_ema_packed_batched.argtypes = [ctypes.POINTER(kfac_ema_packed_item), i32, f32, vp]
+    lib.kfac_factor_diff_workspace_bytes.restype = sz
+    lib.kfac_factor_diff_workspace_bytes.argtypes = [ctypes.POINTER(kfac_diff_item), i32]
+    lib.kfac_factor_diff_batched.restype = ctypes.c_int
+    lib.kfac_factor_diff_batched.argtypes = [ctypes.POINTER(kfac_diff_item), i32, vp, vp, sz, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
@@ -269,6 +278,30 @@ def kfac_ema_packed_batched(batch: PackBatch, decay: float, stream=None) -> None
     """full[i] (a running average) <- decay * full[i] + (1 - decay) * unpack(packed[i])."""
     _check(load_library().kfac_ema_packed_batched(batch.ema_items, batch.count, float(decay), _stream(stream)),
            "kfac_ema_packed_batched")
+
+
+class DiffBatch:
+    """A kfac_diff_item table (host memory), its scratch and its device output (one float per matrix)."""
+
+    def __init__(self, x: Sequence[torch.Tensor], x_prev: Sequence[torch.Tensor], device="cuda"):
+        n = len(x)
+        self.count = n
+        self.keep = (list(x), list(x_prev))
+        self.host = (kfac_diff_item * max(n, 1))()
+        for i in range(n):
+            self.host[i] = kfac_diff_item(x[i].data_ptr(), x_prev[i].data_ptr(), int(x[i].shape[0]))
+        nbytes = int(load_library().kfac_factor_diff_workspace_bytes(self.host, n)) if n else 0
+        self.ws = alloc_workspace(nbytes, device) if nbytes else None
+        self.out = torch.zeros(max(n, 1), dtype=torch.float32, device=device)
+
+
+def kfac_factor_diff_batched(batch: DiffBatch, stream=None) -> torch.Tensor:
+    """out[i] = ||x[i] - x_prev[i]||_F / ||x_prev[i]||_F; returns the device tensor of results."""
+    ws_bytes = 0 if batch.ws is None else batch.ws.numel() * batch.ws.element_size()
+    rc = load_library().kfac_factor_diff_batched(batch.host, batch.count, _ptr(batch.out), _ptr(batch.ws), ws_bytes,
+                                                 _stream(stream))
+    _check(rc, "kfac_factor_diff_batched")
+    return batch.out[:batch.count]
 
 
 def kfac_inverse_workspace_bytes(dim: int) -> int:

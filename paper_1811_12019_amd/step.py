@@ -134,6 +134,16 @@ class KfacNetworkStep:
             l.G_run.copy_(torch.eye(l.shape.d_G, device=l.G_run.device))
 
 
+def refresh_interval(epoch: int) -> int:
+    """Iterations between refreshes of the statistics in epoch e (Sec. 5.4, first heuristic): min(20, 5 floor(e/5) + 1)."""
+    return min(20, 5 * (int(epoch) // 5) + 1)
+
+
+def refresh_interval_late(epoch: int) -> int:
+    """Second heuristic of Sec. 5.4: every iteration before epoch 13, every 20th afterwards."""
+    return 1 if int(epoch) < 13 else 20
+
+
 # Algorithmic work, for rooflines (2 flops per multiply-add; symmetric outputs counted as a triangle).
 def factor_flops(rows: int, dim: int) -> float:
     return float(rows) * dim * (dim + 1)

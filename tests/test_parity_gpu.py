@@ -302,6 +302,31 @@ def test_pack_then_ema_packed_equals_plain_ema():
 
 
 # ----------------------------------------------------------------------------------------------
+# change rate between two refreshes (staleness)
+# ----------------------------------------------------------------------------------------------
+def test_factor_diff_batched():
+    dims = [1, 2, 90, 91, 128, 577, 1025] + [4 + (i % 6) for i in range(126)]        # chunk tails; two launches
+    rng = np.random.default_rng(31)
+    Xp = [rng.standard_normal((d, d)).astype(np.float32) for d in dims]
+    X = [(a + 0.05 * rng.standard_normal(a.shape)).astype(np.float32) for a in Xp]
+    X[3] = Xp[3].copy()                                                             # unchanged statistic: exactly 0
+    X[4] = (2.0 * Xp[4]).astype(np.float32)                                         # doubled: exactly 1
+    xt = [torch.from_numpy(a).to(DEV) for a in X]
+    pt = [torch.from_numpy(a).to(DEV) for a in Xp]
+    batch = kb.DiffBatch(xt, pt, device=DEV)
+    got = kb.kfac_factor_diff_batched(batch).cpu().numpy()
+    torch.cuda.synchronize()
+    want = np.array([ko.factor_diff(a, b) if a.size <= 8192 else np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b.astype(np.float64))
+                     for a, b in zip(X, Xp)])
+    # the big matrices use the library norm (the oracle's element loop takes minutes there); cross-check the two once
+    assert ko.factor_diff(X[2], Xp[2]) == pytest.approx(np.linalg.norm(X[2].astype(np.float64) - Xp[2]) / np.linalg.norm(Xp[2].astype(np.float64)), rel=1e-12)
+    np.testing.assert_allclose(got, want, rtol=2e-6, atol=0)
+    assert got[3] == 0.0 and got[4] == pytest.approx(1.0, rel=1e-6)
+    again = kb.kfac_factor_diff_batched(batch).cpu().numpy()
+    np.testing.assert_array_equal(got, again)                                       # deterministic
+
+
+# ----------------------------------------------------------------------------------------------
 # damped inverse
 # ----------------------------------------------------------------------------------------------
 def gpu_inverse(S, damping):

@@ -3,10 +3,10 @@
 //
 // Packed layout: row i of the upper triangle contributes S[i][i], S[i][i+1], ..., S[i][n-1], rows in order; row i
 // starts at i n - i (i - 1) / 2 and the whole has n (n + 1) / 2 elements.
-// Both kernels work on 64 x 64 tiles (I <= J) of the matrix, one workgroup per tile, all matrices of a call in one
-// launch (workgroup -> matrix through prefix sums in the kernel arguments): a tile row is a contiguous run both in
-// the full matrix and in the packed array, and the mirrored tile of the running average is written row-wise after a
-// transpose through LDS.  HBM bound.
+// All matrices of a call go in one launch (workgroup -> matrix through prefix sums in the kernel arguments).  Packing
+// walks the packed array linearly (aligned 16-byte stores; the sources are runs of matrix rows).  The packed running
+// average works on 64 x 64 tiles (I <= J), one workgroup per tile: a tile row is a contiguous run both in the full
+// matrix and in the packed array, and the mirrored tile is written row-wise after a transpose through LDS.  HBM bound.
 #include "common.h"
 
 namespace kfac {
@@ -56,29 +56,43 @@ __device__ __forceinline__ void pk_store4(gfloat* p, const v4f& v, int valid_fro
         if (e >= valid_from && e < valid_to) p[e] = v[e];
 }
 
-// packed <- upper triangle of full
+// Row of the upper triangle that holds packed element p: the largest i with i n - i (i - 1) / 2 <= p.
+__device__ __forceinline__ int pk_row_of(size_t p, int n) {
+    const double t = 2.0 * n + 1.0;
+    int i = (int)((t - sqrt(t * t - 8.0 * (double)p)) * 0.5);
+    i = max(0, min(i, n - 1));
+    while (i > 0 && pk_row_start(i, n) > p) --i;
+    while (i + 1 < n && pk_row_start(i + 1, n) <= p) ++i;
+    return i;
+}
+
+// packed <- upper triangle of full.  The packed array is walked linearly, four elements (one aligned 16-byte store)
+// per thread; their sources are consecutive in a row of the matrix except where a row ends.
+constexpr unsigned PK_CHUNK = 4096;       // packed elements per workgroup
 __global__ __launch_bounds__(256) void pack_upper_kernel(PackBatch b) {
-    int m, I, J;
-    pk_locate(b, m, I, J);
+    const unsigned wg = blockIdx.x;
+    const int t = threadIdx.x;
+    const int m = __syncthreads_count(t < b.count - 1 && b.prefix[t + 1] <= wg);
     const int n = b.dim[m];
+    const size_t total = (size_t)n * (n + 1) / 2;
     const gfloat* __restrict__ S = as_global(b.full[m]);
     gfloat* __restrict__ P = as_global(b.packed[m]);
-    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
-    const int j = J * PK_T + c4;
-    v4f v[4];
-    int from[4], to[4];
+    const bool aligned = ((uintptr_t)b.packed[m] & 15) == 0;
+    const size_t base = (size_t)(wg - b.prefix[m]) * PK_CHUNK;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int i = I * PK_T + r0 + 16 * p;
-        from[p] = min(4, max(0, i - j));              // columns left of the diagonal are not part of the triangle
-        to[p] = i < n ? min(4, max(0, n - j)) : 0;
-        if (from[p] >= to[p]) { from[p] = to[p] = 0; continue; }
-        v[p] = pk_load4(S + (size_t)i * n + j, from[p], to[p]);
-    }
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int i = I * PK_T + r0 + 16 * p;
-        if (from[p] < to[p]) pk_store4(P + pk_row_start(i, n) + (j - i), v[p], from[p], to[p]);
+    for (int k = 0; k < 4; ++k) {
+        const size_t p = base + (size_t)(k * 256 + t) * 4;
+        if (p >= total) continue;
+        int i = pk_row_of(p, n);
+        int j = i + (int)(p - pk_row_start(i, n));
+        if (aligned && p + 3 < total && j + 3 < n) {
+            *(KFAC_AS1 v4f*)(P + p) = *(const KFAC_AS1 v4f_a4*)(S + (size_t)i * n + j);
+        } else {
+            for (int e = 0; e < 4 && p + e < total; ++e) {
+                P[p + e] = S[(size_t)i * n + j];
+                if (++j == n) { ++i; j = i; }
+            }
+        }
     }
 }
 
@@ -131,7 +145,7 @@ __global__ __launch_bounds__(256) void ema_packed_kernel(PackBatch b, float deca
     }
 }
 
-static int fill_pack(PackBatch& b, const int* dims, float* const* full, float* const* packed, int cnt) {
+static int fill_pack(PackBatch& b, const int* dims, float* const* full, float* const* packed, int cnt, bool tiles) {
     b.count = cnt;
     unsigned wgs = 0;
     for (int i = 0; i < cnt; ++i) {
@@ -139,7 +153,8 @@ static int fill_pack(PackBatch& b, const int* dims, float* const* full, float* c
         b.dim[i] = dims[i];
         b.full[i] = full[i];
         b.packed[i] = packed[i];
-        wgs += (unsigned)pk_tiles(dims[i]);
+        wgs += tiles ? (unsigned)pk_tiles(dims[i])
+                     : (unsigned)(((size_t)dims[i] * (dims[i] + 1) / 2 + PK_CHUNK - 1) / PK_CHUNK);
     }
     b.prefix[cnt] = wgs;
     return (int)wgs;
@@ -170,7 +185,7 @@ extern "C" int kfac_pack_upper_batched(const kfac_pack_item* items_host, int32_t
             packed[i] = items_host[first + i].packed;
         }
         PackBatch b;
-        const int wgs = fill_pack(b, dims, full, packed, cnt);
+        const int wgs = fill_pack(b, dims, full, packed, cnt, false);
         KFAC_LAUNCH(pack_upper_kernel, dim3(wgs), dim3(256), (hipStream_t)stream, b);
     }
     return KFAC_OK;
@@ -191,7 +206,7 @@ extern "C" int kfac_ema_packed_batched(const kfac_ema_packed_item* items_host, i
             packed[i] = const_cast<float*>(items_host[first + i].packed_fresh);
         }
         PackBatch b;
-        const int wgs = fill_pack(b, dims, full, packed, cnt);
+        const int wgs = fill_pack(b, dims, full, packed, cnt, true);
         KFAC_LAUNCH(ema_packed_kernel, dim3(wgs), dim3(256), (hipStream_t)stream, b, decay, 1.0f - decay);
     }
     return KFAC_OK;

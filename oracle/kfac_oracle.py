@@ -183,6 +183,35 @@ def refresh_interval_late(epoch: int) -> int:
     return 1 if int(epoch) < 13 else 20
 
 
+def learning_rate(epoch: float, eta0: float, e_start: float, e_end: float, p_decay: float) -> float:
+    """Polynomial decay of Sec. 4.3: eta0 * (1 - (e - e_start) / (e_end - e_start)) ** p_decay.  The paper defines
+    it between e_start and e_end; before e_start this keeps eta0 and after e_end 0 (reading: the decay has not begun /
+    has finished)."""
+    if epoch <= e_start:
+        return float(eta0)
+    if epoch >= e_end:
+        return 0.0
+    return float(eta0) * (1.0 - (epoch - e_start) / (e_end - e_start)) ** p_decay
+
+
+def momentum_rate(eta: float, eta0: float, m0: float) -> float:
+    """m(e) = m0 / eta0 * eta(e): the ratio momentum / learning rate stays fixed (Sec. 4.3)."""
+    return float(m0) / float(eta0) * float(eta)
+
+
+def weight_update(w, w_prev, precond_grad, eta: float, m: float) -> np.ndarray:
+    """w_next = w - eta * G + m * (w - w_prev), G the preconditioned gradient (Sec. 4.3, the update equation)."""
+    w = np.asarray(w, dtype=np.float64)
+    return w - float(eta) * np.asarray(precond_grad, dtype=np.float64) + float(m) * (w - np.asarray(w_prev, dtype=np.float64))
+
+
+def rescale_weights(w, d_out: int, eps: float = 1e-9) -> np.ndarray:
+    """w <- sqrt(2 d_out) * w / (||w|| + eps), eps = 1e-9 (Sec. 4.4, weights rescaling); ||.|| is the 2-norm of all
+    of the layer's weights."""
+    w = np.asarray(w, dtype=np.float64)
+    return np.sqrt(2.0 * d_out) * w / (np.sqrt(np.sum(w * w)) + eps)
+
+
 def packed_triangle_elems(n: int) -> int:
     """Entries of the upper triangle of an n x n symmetric matrix (Sec. 3.4, symmetry-aware communication)."""
     return n * (n + 1) // 2

@@ -405,3 +405,43 @@ def test_refresh_intervals_worked_values():
     # min(20, 5 floor(e/5) + 1): 1 for epochs 0-4, 6 for 5-9, 11 for 10-14, 16 for 15-19, capped at 20 from epoch 20 on
     assert [ko.refresh_interval(e) for e in (0, 4, 5, 9, 10, 14, 15, 19, 20, 44)] == [1, 1, 6, 6, 11, 11, 16, 16, 20, 20]
     assert [ko.refresh_interval_late(e) for e in (0, 12, 13, 44)] == [1, 1, 20, 20]
+
+
+# ---------------------------------------------------------------------------------------------------
+# optimizer tail: learning rate, momentum, update, rescaling (Sec. 4.3, 4.4)
+# ---------------------------------------------------------------------------------------------------
+def test_learning_rate_and_momentum_schedule_values():
+    # end points and a linear / quadratic midpoint, worked by hand: eta0 = 8, start 1, end 5
+    assert ko.learning_rate(1, 8.0, 1, 5, 2.0) == 8.0
+    assert ko.learning_rate(5, 8.0, 1, 5, 2.0) == 0.0
+    assert ko.learning_rate(3, 8.0, 1, 5, 1.0) == pytest.approx(4.0)          # half way, p = 1
+    assert ko.learning_rate(3, 8.0, 1, 5, 2.0) == pytest.approx(2.0)          # half way, p = 2: 8 * 0.25
+    assert ko.learning_rate(4, 8.0, 1, 5, 3.0) == pytest.approx(8.0 / 64)     # (1/4)^3
+    assert ko.learning_rate(0, 8.0, 1, 5, 2.0) == 8.0
+    # momentum keeps its ratio to the learning rate
+    for e in (1.0, 2.5, 4.0):
+        eta = ko.learning_rate(e, 8.0, 1, 5, 2.0)
+        assert ko.momentum_rate(eta, 8.0, 0.9) / eta == pytest.approx(0.9 / 8.0)
+    assert ko.momentum_rate(8.0, 8.0, 0.9) == pytest.approx(0.9)
+
+
+def test_weight_update_special_cases():
+    rng = np.random.default_rng(9)
+    w, wp, g = rng.standard_normal((3, 5)), rng.standard_normal((3, 5)), rng.standard_normal((3, 5))
+    np.testing.assert_allclose(ko.weight_update(w, wp, g, 0.1, 0.0), w - 0.1 * g)                 # no momentum: plain step
+    np.testing.assert_allclose(ko.weight_update(w, wp, 0 * g, 0.1, 0.5), w + 0.5 * (w - wp))      # no gradient: coasting
+    np.testing.assert_allclose(ko.weight_update(w, w, g, 0.1, 0.9), w - 0.1 * g)                  # no previous motion
+    # scalar case by hand: w = 2, w_prev = 1, G = 4, eta = 0.5, m = 0.25 -> 2 - 2 + 0.25 = 0.25
+    assert ko.weight_update([2.0], [1.0], [4.0], 0.5, 0.25)[0] == pytest.approx(0.25)
+
+
+def test_rescale_weights_norm_and_direction():
+    rng = np.random.default_rng(10)
+    w = rng.standard_normal((64, 577))
+    r = ko.rescale_weights(w, 64)
+    assert np.linalg.norm(r) == pytest.approx(np.sqrt(128.0), rel=1e-9)                          # sqrt(2 d_out)
+    np.testing.assert_allclose(r / np.linalg.norm(r), w / np.linalg.norm(w), atol=1e-15)         # direction kept
+    np.testing.assert_allclose(ko.rescale_weights(7.0 * w, 64), r, rtol=1e-9)                    # scale of w is forgotten
+    assert np.all(ko.rescale_weights(np.zeros((2, 2)), 2) == 0.0)                                # eps keeps 0 / 0 away
+    # 3-4-5 by hand: ||(3, 4)|| = 5, d_out = 2 -> sqrt(4) * (3, 4) / 5
+    np.testing.assert_allclose(ko.rescale_weights([3.0, 4.0], 2), [1.2, 1.6], rtol=1e-9)

@@ -116,8 +116,13 @@ def packed_triangle_rates(net, reps=5):
     pack_batch, ema_batch = kb.PackBatch(full, packed), kb.PackBatch(run, packed)
     dims = [int(t.shape[0]) for t in full]
     diff_batch = kb.DiffBatch(full, run)
+    w = [torch.randn_like(l.P) for l in net.layers]
+    w_prev = [t.clone() for t in w]
+    upd_batch = kb.UpdateBatch(w, w_prev, [l.P for l in net.layers])
+    n_weights = sum(t.numel() for t in w)
     res = {}
     for name, fn, nbytes in (
+            ("weight_update_batched", lambda: kb.kfac_weight_update_batched(upd_batch, 1e-3, 0.9), 28.0 * n_weights),
             ("factor_diff_batched", lambda: kb.kfac_factor_diff_batched(diff_batch), sum(8.0 * d * d for d in dims)),
             ("pack_upper_batched", lambda: kb.kfac_pack_upper_batched(pack_batch), sum(4.0 * d * (d + 1) for d in dims)),
             ("ema_packed_batched", lambda: kb.kfac_ema_packed_batched(ema_batch, 0.95),

@@ -151,6 +151,23 @@ size_t kfac_factor_diff_workspace_bytes(const kfac_diff_item* items_host, int32_
 int kfac_factor_diff_batched(const kfac_diff_item* items_host, int32_t count, float* out, void* ws, size_t ws_bytes,
                              void* stream);
 
+/* Optimizer tail for `count` layers: w_next = w - eta * precond + momentum * (w - w_prev)  (Sec. 4.3, the update
+ * equation), then w_next <- sqrt(2 d_out) * w_next / (||w_next|| + eps)  (Sec. 4.4, weights rescaling; the norm is over
+ * all n weights of the layer).  On return w holds the rescaled w_next and w_prev the old w.  The learning rate and
+ * momentum of the epoch are the caller's (host scalars).  w, w_prev and precond must not overlap.  ws: device scratch
+ * of kfac_weight_update_workspace_bytes bytes, 256-byte aligned.  Deterministic. */
+typedef struct kfac_update_item {
+    float* w;             /* n weights (d_out x d_A), device, updated in place */
+    float* w_prev;        /* n, device, updated in place */
+    const float* precond; /* n, device: the preconditioned gradient */
+    int32_t n;
+    int32_t d_out;
+} kfac_update_item;
+
+size_t kfac_weight_update_workspace_bytes(const kfac_update_item* items_host, int32_t count);
+int kfac_weight_update_batched(const kfac_update_item* items_host, int32_t count, float eta, float momentum, float eps,
+                               void* ws, size_t ws_bytes, void* stream);
+
 /* Workspace for kfac_damped_inverse of one dim x dim matrix. */
 size_t kfac_inverse_workspace_bytes(int32_t dim);
 

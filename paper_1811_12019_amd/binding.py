@@ -29,6 +29,7 @@ EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
     "kfac_ema", "kfac_ema_batched", "kfac_pack_upper_batched", "kfac_ema_packed_batched",
     "kfac_factor_diff_workspace_bytes", "kfac_factor_diff_batched",
+    "kfac_weight_update_workspace_bytes", "kfac_weight_update_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -59,6 +60,11 @@ class kfac_ema_packed_item(ctypes.Structure):
 
 class kfac_diff_item(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("x_prev", ctypes.c_void_p), ("dim", ctypes.c_int32)]
+
+
+class kfac_update_item(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("w_prev", ctypes.c_void_p), ("precond", ctypes.c_void_p),
+                ("n", ctypes.c_int32), ("d_out", ctypes.c_int32)]
 
 
 class kfac_inverse_item(ctypes.Structure):
@@ -115,6 +121,10 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_factor_diff_workspace_bytes.argtypes = [ctypes.POINTER(kfac_diff_item), i32]
     lib.kfac_factor_diff_batched.restype = ctypes.c_int
     lib.kfac_factor_diff_batched.argtypes = [ctypes.POINTER(kfac_diff_item), i32, vp, vp, sz, vp]
+    lib.kfac_weight_update_workspace_bytes.restype = sz
+    lib.kfac_weight_update_workspace_bytes.argtypes = [ctypes.POINTER(kfac_update_item), i32]
+    lib.kfac_weight_update_batched.restype = ctypes.c_int
+    lib.kfac_weight_update_batched.argtypes = [ctypes.POINTER(kfac_update_item), i32, f32, f32, f32, vp, sz, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
@@ -302,6 +312,29 @@ def kfac_factor_diff_batched(batch: DiffBatch, stream=None) -> torch.Tensor:
                                                  _stream(stream))
     _check(rc, "kfac_factor_diff_batched")
     return batch.out[:batch.count]
+
+
+class UpdateBatch:
+    """A kfac_update_item table (host memory) and its scratch; d_out of a layer = rows of its weight matrix."""
+
+    def __init__(self, w: Sequence[torch.Tensor], w_prev: Sequence[torch.Tensor], precond: Sequence[torch.Tensor],
+                 device="cuda"):
+        n = len(w)
+        self.count = n
+        self.keep = (list(w), list(w_prev), list(precond))
+        self.host = (kfac_update_item * max(n, 1))()
+        for i in range(n):
+            self.host[i] = kfac_update_item(w[i].data_ptr(), w_prev[i].data_ptr(), precond[i].data_ptr(),
+                                            int(w[i].numel()), int(w[i].shape[0]))
+        nbytes = int(load_library().kfac_weight_update_workspace_bytes(self.host, n)) if n else 0
+        self.ws = alloc_workspace(nbytes, device) if nbytes else None
+
+
+def kfac_weight_update_batched(batch: UpdateBatch, eta: float, momentum: float, eps: float = 1e-9, stream=None) -> None:
+    ws_bytes = 0 if batch.ws is None else batch.ws.numel() * batch.ws.element_size()
+    rc = load_library().kfac_weight_update_batched(batch.host, batch.count, float(eta), float(momentum), float(eps),
+                                                   _ptr(batch.ws), ws_bytes, _stream(stream))
+    _check(rc, "kfac_weight_update_batched")
 
 
 def kfac_inverse_workspace_bytes(dim: int) -> int:

@@ -144,6 +144,20 @@ def refresh_interval_late(epoch: int) -> int:
     return 1 if int(epoch) < 13 else 20
 
 
+def learning_rate(epoch: float, eta0: float, e_start: float, e_end: float, p_decay: float) -> float:
+    """Polynomial decay of Sec. 4.3 (eta0 before e_start, 0 after e_end)."""
+    if epoch <= e_start:
+        return float(eta0)
+    if epoch >= e_end:
+        return 0.0
+    return float(eta0) * (1.0 - (epoch - e_start) / (e_end - e_start)) ** p_decay
+
+
+def momentum_rate(eta: float, eta0: float, m0: float) -> float:
+    """m(e) = m0 / eta0 * eta(e) (Sec. 4.3)."""
+    return float(m0) / float(eta0) * float(eta)
+
+
 # Algorithmic work, for rooflines (2 flops per multiply-add; symmetric outputs counted as a triangle).
 def factor_flops(rows: int, dim: int) -> float:
     return float(rows) * dim * (dim + 1)

@@ -108,6 +108,13 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_factor_diff_batched(di, 0, None, None, 0, None) == kb.KFAC_OK
     di[1] = kb.kfac_diff_item(0x10000, None, 91)
     assert lib.kfac_factor_diff_batched(di, 2, fake, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    ui = (kb.kfac_update_item * 1)(kb.kfac_update_item(0x10000, 0x20000, 0x30000, 5000, 64))
+    assert lib.kfac_weight_update_workspace_bytes(ui, 1) == 256                          # 2 chunks, one double each
+    assert lib.kfac_weight_update_batched(ui, 1, 0.1, 0.9, 1e-9, None, 0, None) == kb.KFAC_ERR_WORKSPACE
+    assert lib.kfac_weight_update_batched(ui, 1, 0.1, 0.9, -1.0, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    ui[0] = kb.kfac_update_item(0x10000, 0x10010, 0x30000, 5000, 64)                     # w and w_prev overlap
+    assert lib.kfac_weight_update_batched(ui, 1, 0.1, 0.9, 1e-9, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_weight_update_batched(ui, 0, 0.1, 0.9, 1e-9, None, 0, None) == kb.KFAC_OK
 
 
     assert lib.kfac_damped_inverse(fake, 0, 0.1, ctypes.c_void_p(0x9000), None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG
@@ -148,3 +155,7 @@ def test_refresh_interval_helpers_match_the_paper_formulas():
     for e in range(0, 60):
         assert kstep.refresh_interval(e) == ko.refresh_interval(e)
         assert kstep.refresh_interval_late(e) == ko.refresh_interval_late(e)
+    for e in (0.0, 1.0, 2.5, 17.3, 34.9, 35.0, 40.0):
+        eta = kstep.learning_rate(e, 8.18e-3, 1.0, 35.0, 3.5)
+        assert eta == ko.learning_rate(e, 8.18e-3, 1.0, 35.0, 3.5)
+        assert kstep.momentum_rate(eta, 8.18e-3, 0.997) == ko.momentum_rate(eta, 8.18e-3, 0.997)

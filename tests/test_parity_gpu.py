@@ -327,6 +327,29 @@ def test_factor_diff_batched():
 
 
 # ----------------------------------------------------------------------------------------------
+# optimizer tail: weight update with momentum, then rescaling
+# ----------------------------------------------------------------------------------------------
+def test_weight_update_batched():
+    shapes = [(1, 1), (16, 145), (64, 148), (64, 577), (130, 129), (1000, 2049)] + [(3 + i % 4, 5 + i % 7) for i in range(125)]
+    rng = np.random.default_rng(41)
+    W = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    Wp = [(w + 0.01 * rng.standard_normal(w.shape)).astype(np.float32) for w in W]
+    P = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    wt, wpt, pt = ([torch.from_numpy(a.copy()).to(DEV) for a in L] for L in (W, Wp, P))
+    eta, mom = 0.02, 0.9 * 0.02 / 8.18e-3
+    kb.kfac_weight_update_batched(kb.UpdateBatch(wt, wpt, pt, device=DEV), eta, mom)
+    torch.cuda.synchronize()
+    for w, wp, p, a, b, c in zip(W, Wp, P, wt, wpt, pt):
+        want = ko.rescale_weights(ko.weight_update(w, wp, p, np.float32(eta), np.float32(mom)), w.shape[0])
+        got = a.cpu().numpy()
+        np.testing.assert_allclose(got, want, rtol=0, atol=3e-6 * np.abs(want).max())
+        assert np.linalg.norm(got.astype(np.float64)) == pytest.approx(np.sqrt(2.0 * w.shape[0]), rel=1e-5)
+        np.testing.assert_array_equal(b.cpu().numpy(), w)            # w_prev <- old w, bit for bit
+        np.testing.assert_array_equal(c.cpu().numpy(), p)            # the preconditioned gradient is only read
+    kb.kfac_weight_update_batched(kb.UpdateBatch([], [], [], device=DEV), eta, mom)
+
+
+# ----------------------------------------------------------------------------------------------
 # damped inverse
 # ----------------------------------------------------------------------------------------------
 def gpu_inverse(S, damping):

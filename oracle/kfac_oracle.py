@@ -183,6 +183,44 @@ def refresh_interval_late(epoch: int) -> int:
     return 1 if int(epoch) < 13 else 20
 
 
+# ---- Batch Normalization layers (Sec. 5.4: their Fisher matrix is not factorised; full or diagonal) -----------------
+# The paper gives no formula.  Reading: a BN layer with C channels has parameters theta = (scale_1..scale_C,
+# shift_1..shift_C); with xhat the normalised input and gout the gradient w.r.t. the layer's output, the gradient of
+# sample n is  d/d scale_c = sum_{y,x} gout[n,c,y,x] xhat[n,c,y,x],  d/d shift_c = sum_{y,x} gout[n,c,y,x];  the
+# Fisher matrix is the mini-batch mean of the outer products of these per-sample gradients (the same empirical
+# estimate the conv factors are built from), 2C x 2C, or only its diagonal.
+def bn_sample_grads(xhat, gout) -> np.ndarray:
+    """Per-sample gradients of a BN layer's (scale, shift): (N, C, H, W) x 2 -> (N, 2C)."""
+    xhat = np.asarray(xhat, dtype=np.float64)
+    gout = np.asarray(gout, dtype=np.float64)
+    d_scale = (gout * xhat).sum(axis=(2, 3))
+    d_shift = gout.sum(axis=(2, 3))
+    return np.concatenate([d_scale, d_shift], axis=1)
+
+
+def bn_fisher(sample_grads) -> np.ndarray:
+    """F = (1/N) sum_n g_n g_n^T, 2C x 2C ("no approx" in Sec. 5.4)."""
+    g = np.asarray(sample_grads, dtype=np.float64)
+    return g.T @ g / g.shape[0]
+
+
+def bn_fisher_diag(sample_grads) -> np.ndarray:
+    """diag(F): (1/N) sum_n g_n,i^2 (the diagonal approximation of Sec. 5.4)."""
+    g = np.asarray(sample_grads, dtype=np.float64)
+    return (g * g).sum(axis=0) / g.shape[0]
+
+
+def bn_precondition_diag(fisher_diag, grad, damping: float) -> np.ndarray:
+    """(diag(F) + damping I)^-1 grad, element-wise; damping = rho_BN * gamma (Sec. 4.2)."""
+    return np.asarray(grad, dtype=np.float64) / (np.asarray(fisher_diag, dtype=np.float64) + float(damping))
+
+
+def bn_precondition_full(fisher, grad, damping: float) -> np.ndarray:
+    """(F + damping I)^-1 grad."""
+    F = np.asarray(fisher, dtype=np.float64)
+    return np.linalg.solve(F + float(damping) * np.eye(F.shape[0]), np.asarray(grad, dtype=np.float64))
+
+
 def learning_rate(epoch: float, eta0: float, e_start: float, e_end: float, p_decay: float) -> float:
     """Polynomial decay of Sec. 4.3: eta0 * (1 - (e - e_start) / (e_end - e_start)) ** p_decay.  The paper defines
     it between e_start and e_end; before e_start this keeps eta0 and after e_end 0 (reading: the decay has not begun /

@@ -445,3 +445,48 @@ def test_rescale_weights_norm_and_direction():
     assert np.all(ko.rescale_weights(np.zeros((2, 2)), 2) == 0.0)                                # eps keeps 0 / 0 away
     # 3-4-5 by hand: ||(3, 4)|| = 5, d_out = 2 -> sqrt(4) * (3, 4) / 5
     np.testing.assert_allclose(ko.rescale_weights([3.0, 4.0], 2), [1.2, 1.6], rtol=1e-9)
+
+
+# ---------------------------------------------------------------------------------------------------
+# Batch Normalization layers: per-sample gradients, full / diagonal Fisher matrix (Sec. 5.4)
+# ---------------------------------------------------------------------------------------------------
+def test_bn_sample_grads_match_autograd_per_sample():
+    torch.manual_seed(0)
+    N, C, H, W = 3, 4, 5, 2
+    xhat = torch.randn(N, C, H, W, dtype=torch.float64)
+    gout = torch.randn(N, C, H, W, dtype=torch.float64)
+    got = ko.bn_sample_grads(xhat.numpy(), gout.numpy())
+    assert got.shape == (N, 2 * C)
+    for n in range(N):
+        scale = torch.ones(C, dtype=torch.float64, requires_grad=True)
+        shift = torch.zeros(C, dtype=torch.float64, requires_grad=True)
+        y = scale.view(1, C, 1, 1) * xhat[n:n + 1] + shift.view(1, C, 1, 1)
+        (y * gout[n:n + 1]).sum().backward()                      # dL/dy = gout
+        np.testing.assert_allclose(got[n, :C], scale.grad.numpy(), rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(got[n, C:], shift.grad.numpy(), rtol=1e-13, atol=1e-13)
+
+
+def test_bn_fisher_brute_force_and_diagonal():
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal((5, 6))
+    F = np.zeros((6, 6))
+    for n in range(5):
+        for i in range(6):
+            for j in range(6):
+                F[i, j] += g[n, i] * g[n, j] / 5
+    np.testing.assert_allclose(ko.bn_fisher(g), F, rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(ko.bn_fisher_diag(g), np.diag(F), rtol=1e-14)
+    # ResNet-50: full BN blocks (2C)^2 floats add up to the paper's 1017 - 587 MiB
+    total = sum((2 * c) ** 2 * 4 for c in synth.resnet50_bn_channels())
+    assert total / 2 ** 20 == pytest.approx(1017 - 587, abs=1.0)
+
+
+def test_bn_precondition_diag_and_full():
+    rng = np.random.default_rng(13)
+    g = rng.standard_normal((40, 8))
+    F, grad = ko.bn_fisher(g), rng.standard_normal(8)
+    full = ko.bn_precondition_full(F, grad, 0.1)
+    np.testing.assert_allclose((F + 0.1 * np.eye(8)) @ full, grad, rtol=1e-12, atol=1e-13)
+    # a diagonal Fisher matrix: both forms agree; by hand: diag (1, 3), grad (2, 2), damping 1 -> (1, 0.5)
+    np.testing.assert_allclose(ko.bn_precondition_diag([1.0, 3.0], [2.0, 2.0], 1.0), [1.0, 0.5])
+    np.testing.assert_allclose(ko.bn_precondition_full(np.diag([1.0, 3.0]), [2.0, 2.0], 1.0), [1.0, 0.5])

@@ -120,8 +120,20 @@ def packed_triangle_rates(net, reps=5):
     w_prev = [t.clone() for t in w]
     upd_batch = kb.UpdateBatch(w, w_prev, [l.P for l in net.layers])
     n_weights = sum(t.numel() for t in w)
+    # Batch Normalization layers behind the 53 convolutions: normalised input and output gradient, bf16 NHWC
+    bn_x, bn_g = [], []
+    for l in net.layers:
+        s = l.shape
+        if s.kh * s.kw == 1 and s.H == 1:                # the fc layer has none
+            continue
+        x = torch.randn((s.N, s.H_out, s.W_out, s.C_out), device=l.P.device).to(torch.bfloat16)
+        bn_x.append(x)
+        bn_g.append((0.01 * torch.randn_like(x, dtype=torch.float32)).to(torch.bfloat16))
+    bn_batch = kb.BnBatch(bn_x, bn_g, kb.KFAC_BF16, bn_x[0].device)
+
     res = {}
     for name, fn, nbytes in (
+            ("bn_sample_grads_batched", lambda: kb.kfac_bn_sample_grads_batched(bn_batch), sum(4.0 * x.numel() for x in bn_x)),
             ("weight_update_batched", lambda: kb.kfac_weight_update_batched(upd_batch, 1e-3, 0.9), 28.0 * n_weights),
             ("factor_diff_batched", lambda: kb.kfac_factor_diff_batched(diff_batch), sum(8.0 * d * d for d in dims)),
             ("pack_upper_batched", lambda: kb.kfac_pack_upper_batched(pack_batch), sum(4.0 * d * (d + 1) for d in dims)),

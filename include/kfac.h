@@ -168,6 +168,35 @@ size_t kfac_weight_update_workspace_bytes(const kfac_update_item* items_host, in
 int kfac_weight_update_batched(const kfac_update_item* items_host, int32_t count, float eta, float momentum, float eps,
                                void* ws, size_t ws_bytes, void* stream);
 
+/* Batch Normalization layers (Sec. 5.4: their Fisher matrix is not Kronecker-factorised).  Per-sample gradients of a
+ * BN layer's parameters theta = (scale_1..scale_C, shift_1..shift_C):
+ *     g[n][c] = sum_s gout[n][s][c] * xhat[n][s][c],   g[n][C + c] = sum_s gout[n][s][c],   s = 0..HW-1,
+ * from the normalised input xhat and the output gradient gout, both N x HW x C (channels last), dtype kfac_dtype.
+ * g: N x 2C floats, device.  ws: kfac_bn_sample_grads_workspace_bytes bytes, 256-byte aligned.  Deterministic.
+ * The full Fisher matrix F = (1/N) sum_n g_n g_n^T is kfac_factor_G on g seen as an N x 2C x 1 x 1 fp32 tensor, its
+ * damped inverse kfac_damped_inverse, and F^-1 grad kfac_precondition with dG = 1. */
+size_t kfac_bn_sample_grads_workspace_bytes(int32_t N, int32_t C, int32_t HW);   /* may be 0: then ws may be NULL */
+int kfac_bn_sample_grads(const void* xhat, const void* gout, int32_t N, int32_t C, int32_t HW, int32_t dtype, float* g,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* The same for many layers at once (all BN layers of a network in two or three launches).  items_host: host array,
+ * read during the call only; the tensors it names are device memory.  Layers may differ in every field. */
+typedef struct {
+    const void* xhat;
+    const void* gout;
+    float* g;
+    int32_t N, C, HW;
+    int32_t dtype;   /* kfac_dtype */
+} kfac_bn_item;
+
+size_t kfac_bn_sample_grads_batched_workspace_bytes(const kfac_bn_item* items_host, int32_t count);
+int kfac_bn_sample_grads_batched(const kfac_bn_item* items_host, int32_t count, void* ws, size_t ws_bytes, void* stream);
+
+/* Diagonal approximation (Sec. 5.4): fisher_diag[j] = (1/N) sum_n g[n][j]^2 and out[j] = grad[j] / (fisher_diag[j] +
+ * damping), j < C2 = 2C; damping = rho_BN * gamma (Sec. 4.2).  Either output may be NULL (grad may be NULL if out is). */
+int kfac_bn_diag_precondition(const float* g, int32_t N, int32_t C2, const float* grad, float damping,
+                              float* fisher_diag, float* out, void* stream);
+
 /* Workspace for kfac_damped_inverse of one dim x dim matrix. */
 size_t kfac_inverse_workspace_bytes(int32_t dim);
 

@@ -30,6 +30,8 @@ EXPORTED_SYMBOLS = (
     "kfac_ema", "kfac_ema_batched", "kfac_pack_upper_batched", "kfac_ema_packed_batched",
     "kfac_factor_diff_workspace_bytes", "kfac_factor_diff_batched",
     "kfac_weight_update_workspace_bytes", "kfac_weight_update_batched",
+    "kfac_bn_sample_grads_workspace_bytes", "kfac_bn_sample_grads", "kfac_bn_diag_precondition",
+    "kfac_bn_sample_grads_batched_workspace_bytes", "kfac_bn_sample_grads_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
@@ -60,6 +62,11 @@ class kfac_ema_packed_item(ctypes.Structure):
 
 class kfac_diff_item(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("x_prev", ctypes.c_void_p), ("dim", ctypes.c_int32)]
+
+
+class kfac_bn_item(ctypes.Structure):
+    _fields_ = [("xhat", ctypes.c_void_p), ("gout", ctypes.c_void_p), ("g", ctypes.c_void_p), ("N", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("HW", ctypes.c_int32), ("dtype", ctypes.c_int32)]
 
 
 class kfac_update_item(ctypes.Structure):
@@ -125,6 +132,16 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_weight_update_workspace_bytes.argtypes = [ctypes.POINTER(kfac_update_item), i32]
     lib.kfac_weight_update_batched.restype = ctypes.c_int
     lib.kfac_weight_update_batched.argtypes = [ctypes.POINTER(kfac_update_item), i32, f32, f32, f32, vp, sz, vp]
+    lib.kfac_bn_sample_grads_workspace_bytes.restype = sz
+    lib.kfac_bn_sample_grads_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.kfac_bn_sample_grads.restype = ctypes.c_int
+    lib.kfac_bn_sample_grads.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.kfac_bn_sample_grads_batched_workspace_bytes.restype = sz
+    lib.kfac_bn_sample_grads_batched_workspace_bytes.argtypes = [ctypes.POINTER(kfac_bn_item), i32]
+    lib.kfac_bn_sample_grads_batched.restype = ctypes.c_int
+    lib.kfac_bn_sample_grads_batched.argtypes = [ctypes.POINTER(kfac_bn_item), i32, vp, sz, vp]
+    lib.kfac_bn_diag_precondition.restype = ctypes.c_int
+    lib.kfac_bn_diag_precondition.argtypes = [vp, i32, i32, vp, f32, vp, vp, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
@@ -335,6 +352,62 @@ def kfac_weight_update_batched(batch: UpdateBatch, eta: float, momentum: float, 
     rc = load_library().kfac_weight_update_batched(batch.host, batch.count, float(eta), float(momentum), float(eps),
                                                    _ptr(batch.ws), ws_bytes, _stream(stream))
     _check(rc, "kfac_weight_update_batched")
+
+
+def kfac_bn_sample_grads_workspace_bytes(N: int, C: int, HW: int) -> int:
+    return int(load_library().kfac_bn_sample_grads_workspace_bytes(int(N), int(C), int(HW)))
+
+
+def kfac_bn_sample_grads(xhat: torch.Tensor, gout: torch.Tensor, dtype: int, g: Optional[torch.Tensor] = None,
+                         ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """xhat, gout: (N, H, W, C) or (N, HW, C) channels-last tensors of the given kfac dtype; returns g (N, 2C) fp32."""
+    N, C = int(xhat.shape[0]), int(xhat.shape[-1])
+    HW = int(xhat.numel() // (N * C))
+    if g is None:
+        g = torch.empty((N, 2 * C), dtype=torch.float32, device=xhat.device)
+    if ws is None:
+        ws = alloc_workspace(int(load_library().kfac_bn_sample_grads_workspace_bytes(N, C, HW)), xhat.device)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().kfac_bn_sample_grads(_ptr(xhat), _ptr(gout), N, C, HW, int(dtype), _ptr(g), _ptr(ws), ws_bytes,
+                                             _stream(stream))
+    _check(rc, "kfac_bn_sample_grads")
+    return g
+
+
+class BnBatch:
+    """A kfac_bn_item table (host memory), the per-sample gradient tensors (N, 2C) and the scratch, for many BN layers.
+    xhat[i], gout[i]: channels-last (N, H, W, C) or (N, HW, C) tensors of kfac dtype dtype[i] (one value: all layers)."""
+
+    def __init__(self, xhat: Sequence[torch.Tensor], gout: Sequence[torch.Tensor], dtype, device="cuda"):
+        n = len(xhat)
+        dtypes = list(dtype) if isinstance(dtype, (list, tuple)) else [int(dtype)] * n
+        self.count = n
+        self.g = []
+        self.host = (kfac_bn_item * max(n, 1))()
+        for i in range(n):
+            N, C = int(xhat[i].shape[0]), int(xhat[i].shape[-1])
+            HW = int(xhat[i].numel() // (N * C))
+            self.g.append(torch.empty((N, 2 * C), dtype=torch.float32, device=device))
+            self.host[i] = kfac_bn_item(xhat[i].data_ptr(), gout[i].data_ptr(), self.g[i].data_ptr(), N, C, HW, dtypes[i])
+        self.keep = (list(xhat), list(gout))
+        nbytes = int(load_library().kfac_bn_sample_grads_batched_workspace_bytes(self.host, n)) if n else 0
+        self.ws = alloc_workspace(nbytes, device) if nbytes else None
+
+
+def kfac_bn_sample_grads_batched(batch: BnBatch, stream=None):
+    ws_bytes = 0 if batch.ws is None else batch.ws.numel() * batch.ws.element_size()
+    rc = load_library().kfac_bn_sample_grads_batched(batch.host, batch.count, _ptr(batch.ws), ws_bytes, _stream(stream))
+    _check(rc, "kfac_bn_sample_grads_batched")
+    return batch.g
+
+
+def kfac_bn_diag_precondition(g: torch.Tensor, grad: Optional[torch.Tensor], damping: float,
+                              fisher_diag: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                              stream=None) -> None:
+    N, C2 = int(g.shape[0]), int(g.shape[1])
+    rc = load_library().kfac_bn_diag_precondition(_ptr(g), N, C2, _ptr(grad), float(damping), _ptr(fisher_diag), _ptr(out),
+                                                  _stream(stream))
+    _check(rc, "kfac_bn_diag_precondition")
 
 
 def kfac_inverse_workspace_bytes(dim: int) -> int:

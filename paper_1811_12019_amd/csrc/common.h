@@ -27,6 +27,16 @@
         if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;                  \
     } while (0)
 
+// Same, with `lds` bytes of dynamic LDS.
+#define KFAC_LAUNCH_LDS(kernel, grid, block, lds, stream, ...)                     \
+    do {                                                                           \
+        void* tok__ = nullptr;                                                     \
+        if (kfac::timing_enabled()) kfac::timing_begin(#kernel, stream, &tok__);   \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);         \
+        if (tok__) kfac::timing_end(stream, tok__);                                \
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;                  \
+    } while (0)
+
 namespace kfac {
 
 // Opt-in per-kernel event timing (runtime.hip).

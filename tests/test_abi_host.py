@@ -115,6 +115,19 @@ def test_bad_arguments_are_rejected_on_the_host():
     ui[0] = kb.kfac_update_item(0x10000, 0x10010, 0x30000, 5000, 64)                     # w and w_prev overlap
     assert lib.kfac_weight_update_batched(ui, 1, 0.1, 0.9, 1e-9, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_weight_update_batched(ui, 0, 0.1, 0.9, 1e-9, None, 0, None) == kb.KFAC_OK
+    assert lib.kfac_bn_sample_grads_workspace_bytes(2, 64, 552) == 2 * 2 * 128 * 4         # two chunks of 512 positions
+    assert lib.kfac_bn_sample_grads(fake, fake, 2, 64, 552, kb.KFAC_BF16, fake, None, 0, None) == kb.KFAC_ERR_WORKSPACE
+    assert lib.kfac_bn_sample_grads(None, fake, 2, 64, 552, kb.KFAC_BF16, fake, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_bn_sample_grads(fake, fake, 2, 64, 552, 7, fake, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    bi = (kb.kfac_bn_item * 2)(kb.kfac_bn_item(0x1000, 0x1000, 0x1000, 2, 64, 552, kb.KFAC_BF16),
+                               kb.kfac_bn_item(0x1000, 0x1000, 0x1000, 2, 2048, 49, kb.KFAC_BF16))
+    assert lib.kfac_bn_sample_grads_batched_workspace_bytes(bi, 2) == 2048                  # the second layer is one chunk
+    assert lib.kfac_bn_sample_grads_batched(bi, 2, None, 0, None) == kb.KFAC_ERR_WORKSPACE
+    assert lib.kfac_bn_sample_grads_batched(bi, 0, None, 0, None) == kb.KFAC_OK
+    bi[1].C = 0
+    assert lib.kfac_bn_sample_grads_batched(bi, 2, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_bn_diag_precondition(fake, 2, 128, None, 0.1, None, fake, None) == kb.KFAC_ERR_INVALID_ARG   # out without grad
+    assert lib.kfac_bn_diag_precondition(fake, 2, 128, fake, -0.1, fake, fake, None) == kb.KFAC_ERR_INVALID_ARG
 
 
     assert lib.kfac_damped_inverse(fake, 0, 0.1, ctypes.c_void_p(0x9000), None, None, 0, None) == kb.KFAC_ERR_INVALID_ARG

@@ -350,6 +350,83 @@ def test_weight_update_batched():
 
 
 # ----------------------------------------------------------------------------------------------
+# Batch Normalization layers: per-sample gradients, diagonal and full Fisher matrix
+# ----------------------------------------------------------------------------------------------
+def _bn_inputs(N, C, H, W, dtype, seed):
+    rng = np.random.default_rng([seed, N, C, H, W])
+    rnd = _NP_ROUND[dtype]
+    xhat = rnd(rng.standard_normal((N, C, H, W)))                   # a normalised activation: N(0, 1)
+    gout = rnd(synth.SIGMA_GOUT * rng.standard_normal((N, C, H, W)))
+    td = kb._TORCH_DTYPE[dtype]
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a.transpose(0, 2, 3, 1))).to(DEV).to(td).contiguous()
+    return xhat, gout, to_dev(xhat), to_dev(gout)
+
+
+@pytest.mark.parametrize("N,C,H,W,dtype", [
+    (4, 64, 23, 24, kb.KFAC_BF16),        # 552 positions: two chunks, 32 position lanes
+    (3, 192, 9, 9, kb.KFAC_F16),          # 24 vectors per position: idle threads
+    (2, 2048, 7, 7, kb.KFAC_BF16),        # widest ResNet-50 BN layer
+    (2, 2056, 3, 3, kb.KFAC_BF16),        # more than 256 vectors per position, ragged
+    (3, 5, 6, 7, kb.KFAC_BF16),           # channels not a multiple of 8: general kernel
+    (2, 16, 5, 5, kb.KFAC_F32),
+])
+def test_bn_sample_grads(N, C, H, W, dtype):
+    xhat, gout, xt, gt = _bn_inputs(N, C, H, W, dtype, 51)
+    g = kb.kfac_bn_sample_grads(xt, gt, dtype)
+    torch.cuda.synchronize()
+    want = ko.bn_sample_grads(xhat, gout)
+    assert g.shape == (N, 2 * C)
+    np.testing.assert_allclose(g.cpu().numpy(), want, rtol=0, atol=2e-6 * np.abs(want).max())
+
+
+def test_bn_sample_grads_batched_mixed_layers():
+    cases = [(4, 64, 23, 24, kb.KFAC_BF16), (2, 2048, 7, 7, kb.KFAC_BF16), (3, 192, 9, 9, kb.KFAC_F16), (3, 5, 6, 7, kb.KFAC_BF16),
+             (2, 16, 33, 32, kb.KFAC_F32), (5, 256, 14, 14, kb.KFAC_BF16), (2, 1032, 2, 3, kb.KFAC_F16)]
+    ins = [_bn_inputs(*c, 54 + i) for i, c in enumerate(cases)]
+    batch = kb.BnBatch([t[2] for t in ins], [t[3] for t in ins], [c[4] for c in cases], DEV)
+    for rep in range(2):                                             # the scratch is reused: a second call gives the same
+        gs = kb.kfac_bn_sample_grads_batched(batch)
+        torch.cuda.synchronize()
+        for (xhat, gout, _, _), g in zip(ins, gs):
+            want = ko.bn_sample_grads(xhat, gout)
+            np.testing.assert_allclose(g.cpu().numpy(), want, rtol=0, atol=2e-6 * np.abs(want).max())
+
+
+def test_bn_diag_and_full_fisher_preconditioning():
+    N, C, H, W = 32, 64, 14, 14
+    xhat, gout, xt, gt = _bn_inputs(N, C, H, W, kb.KFAC_BF16, 52)
+    g = kb.kfac_bn_sample_grads(xt, gt, kb.KFAC_BF16)
+    rng = np.random.default_rng(53)
+    grad = rng.standard_normal(2 * C).astype(np.float32)
+    gradt = torch.from_numpy(grad).to(DEV)
+    damping = 10.0 * 1e-3                                            # rho_BN * gamma
+    fd, out = torch.empty(2 * C, device=DEV), torch.empty(2 * C, device=DEV)
+    kb.kfac_bn_diag_precondition(g, gradt, damping, fd, out)
+    torch.cuda.synchronize()
+    g64 = g.cpu().numpy().astype(np.float64)                         # each stage against the oracle on the GPU stage's input
+    np.testing.assert_allclose(fd.cpu().numpy(), ko.bn_fisher_diag(g64), rtol=2e-6)
+    np.testing.assert_allclose(out.cpu().numpy(), ko.bn_precondition_diag(ko.bn_fisher_diag(g64), grad, np.float32(damping)), rtol=1e-5)
+    # full 2C x 2C Fisher matrix through the generic entry points: factor of the (N x 2C) gradient matrix, damped
+    # inverse, product with the gradient as a 1 x 2C matrix
+    shp = synth.LayerShape("bn.full", N, 1, 1, 1, 2 * C, 1, 1, 1, 0)
+    desc = kb.make_desc(shp, kb.KFAC_NHWC, kb.KFAC_F32, kb.KFAC_ORDER_KH_KW_C)
+    F = torch.empty((2 * C, 2 * C), device=DEV)
+    kb.kfac_factor_G(desc, g, 0.0, F, kb.alloc_workspace(kb.kfac_factor_workspace_bytes(kb.KFAC_OP_FACTOR_G, desc), DEV))
+    Finv = torch.empty_like(F)
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    kb.kfac_damped_inverse(F, 2 * C, damping, Finv, info, kb.alloc_workspace(kb.kfac_inverse_workspace_bytes(2 * C)))
+    one = torch.ones((1, 1), device=DEV)
+    P = torch.empty((1, 2 * C), device=DEV)
+    kb.kfac_precondition(one, Finv, gradt.view(1, -1), 1, 2 * C, P, kb.alloc_workspace(kb.kfac_precondition_workspace_bytes(1, 2 * C)))
+    torch.cuda.synchronize()
+    assert int(info) == 0
+    assert rel_fro(F.cpu().numpy(), ko.bn_fisher(g64)) < FACTOR_TOL
+    want = ko.bn_precondition_full(F.cpu().numpy().astype(np.float64), grad, float(np.float32(damping)))
+    assert rel_fro(P.cpu().numpy().ravel(), want) < PRE_TOL
+    np.testing.assert_allclose(np.diag(F.cpu().numpy()), fd.cpu().numpy(), rtol=1e-5)      # the diagonal form is its diagonal
+
+
+# ----------------------------------------------------------------------------------------------
 # damped inverse
 # ----------------------------------------------------------------------------------------------
 def gpu_inverse(S, damping):

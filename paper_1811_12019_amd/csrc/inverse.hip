@@ -202,59 +202,20 @@ __device__ __forceinline__ int invert16_wave(const float* __restrict__ D16, int 
     return bad;
 }
 
-// from_S: single-block matrix, read S + lambda I and write the caller's output directly.
-__global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int from_S) {
-    __shared__ float sD[NB * (NB + 1)];
-    __shared__ __attribute__((aligned(16))) float Us[NB * PLD];
-    __shared__ __attribute__((aligned(16))) float Ts[NB * PLD];
-    __shared__ __attribute__((aligned(16))) float Ps[PSB * PLD];
-    __shared__ int bad;
-    const int m = blockIdx.x;
-    const Item it = get_item(b, m);
-    const int d = it.dim;
-    const int k0 = step * NB;
-    const int nb = min(NB, d - k0);
-    const bool last = k0 + NB >= d;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int lm = lane & 31, h = lane >> 5;
-    const WsView ws = ws_view(it.ws, d);
-    if (t == 0) bad = 0;
+// LDS of the pivot code: the block's packed lower triangle (row r holds columns 0..r) while it is brought into or
+// out of the registers, and the sweep's panels in between, in the same memory.
+constexpr int TRI_FLOATS = NB * (NB + 1) / 2;                        // 33,024 bytes
+constexpr int PIV_US = 0, PIV_TS = NB * PLD, PIV_PS = 2 * NB * PLD, PIV_BAD = PIV_PS + PSB * PLD;
+constexpr int PIV_LDS_FLOATS = TRI_FLOATS;
+static_assert(PIV_BAD + 1 <= PIV_LDS_FLOATS, "the sweep's panels must fit the triangle's memory");
 
-    // ---- load: lower triangle, row-wise, into sD; identity outside the block.  All loads are issued before the
-    //      first LDS store so that the block costs one memory round trip, not one per row group ----
-    {
-        const int c4 = (t & 31) * 4, r0 = t >> 5;        // 8 rows x 32 float4 per pass, 16 passes
-        const bool vec_ok = !from_S;                     // the padded working copy is 16-byte aligned, S need not be
-        v4f v[16];
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const int row = r0 + 8 * p;
-            v4f x = {0.f, 0.f, 0.f, 0.f};
-            if (row < nb && c4 <= row) {
-                if (vec_ok) {
-                    x = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4];
-                } else {
-                    const gfloat* src = it.S + (size_t)(k0 + row) * d + k0 + c4;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (c4 + i <= row) x[i] = src[i] + (c4 + i == row ? it.damping : 0.f);
-                }
-            }
-            v[p] = x;
-        }
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const int row = r0 + 8 * p;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int c = c4 + i;
-                const bool in = row < nb && c <= row;
-                sD[row * (NB + 1) + c] = in ? v[p][i] : (row == c ? 1.f : 0.f);
-            }
-        }
-    }
-    __syncthreads();
-    v16f acc[2][2];
+__device__ __forceinline__ int tri_at(int r, int c) { return ((r * (r + 1)) >> 1) + c; }          // r >= c
+__device__ __forceinline__ int tri_sym(int r, int c) { return r >= c ? tri_at(r, c) : tri_at(c, r); }
+
+// D (accumulator layout, all four quadrants) <- the symmetric block whose lower triangle is in tri, bordered by the
+// identity beyond nb.  Ends with a barrier: tri may be overwritten afterwards.
+__device__ __forceinline__ void pivot_fill(v16f (&acc)[2][2], const float* __restrict__ tri, int nb) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -262,15 +223,26 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                acc[mb][nbk][r] = sD[max(row, col) * (NB + 1) + min(row, col)];
+                acc[mb][nbk][r] = (row < nb && col < nb) ? tri[tri_sym(row, col)] : (row == col ? 1.f : 0.f);
             }
+    __syncthreads();
+}
 
+// The symmetric sweep of D in 16-wide sub-blocks (see above); lds: PIV_LDS_FLOATS floats.  Returns (to every thread)
+// the 1-based index inside the block of the first non-positive pivot, or 0.  Ends with a barrier.
+__device__ __forceinline__ int pivot_sweep(v16f (&acc)[2][2], int nb, float* __restrict__ lds) {
+    float* __restrict__ Us = lds + PIV_US;
+    float* __restrict__ Ts = lds + PIV_TS;
+    float* __restrict__ Ps = lds + PIV_PS;
+    int* bad = (int*)(lds + PIV_BAD);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    if (t == 0) *bad = 0;
     const int trow = t >> 1, tc0 = (t & 1) * 8;      // T16: thread -> one row, 8 of the 16 columns
 #pragma unroll
     for (int jb = 0; jb < NB / PSB; ++jb) {
         const int j0 = jb * PSB;
         if (j0 >= nb) break;                         // uniform
-        constexpr int dummy = 0; (void)dummy;
         const int own_w = jb >> 2;                   // wn (for columns) / wm (for rows) that owns sub-block jb
         const int own_b = (jb >> 1) & 1;             // nbk / mb inside the quadrant
         const int own_h = jb & 1;                    // which 16 of the block's 32
@@ -287,7 +259,7 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
         // 2. P16
         if (wave == 0) {
             const int f = invert16_wave(Us + j0 * PLD, PLD, Ps);
-            if (f != 0 && lane == 0 && bad == 0) bad = k0 + j0 + f;
+            if (f != 0 && lane == 0 && *bad == 0) *bad = j0 + f;
         }
         __syncthreads();
         // 3. T16 = U16 . P16, rows of the sub-block replaced by -P16
@@ -353,14 +325,18 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
         }
     }
     __syncthreads();
-    if (t == 0 && it.info) {
-        if (from_S) *it.info = bad;                             // single-block matrix: this is its only kernel
-        else if (bad != 0) atomicCAS((int*)it.info, 0, bad);    // keep the first failing minor
-    }
+    const int f = *bad;
+    __syncthreads();                                 // everybody has read the flag: the memory may be reused
+    return f;
+}
 
-    // D now holds -P up to rounding asymmetry; take the lower triangle as the truth so that P is exactly
-    // symmetric.  The working copy gets -P; on the last step the caller's output gets +P (the final sign flip).
-    // The workspace gets +P for the panel product.
+// D holds -P up to rounding asymmetry; its lower triangle is taken as the truth so that P is exactly symmetric.
+// The working copy gets -P; on the matrix's last step the caller's output gets +P (the final sign flip) instead.
+// The workspace gets +P for the panel product.
+__device__ __forceinline__ void pivot_write(const v16f (&acc)[2][2], float* __restrict__ tri, const Item& it,
+                                            const WsView& ws, int k0, int nb, bool last, bool from_S) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int d = it.dim;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -368,33 +344,82 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                if (row >= col) sD[row * (NB + 1) + col] = acc[mb][nbk][r];
+                if (row >= col) tri[tri_at(row, col)] = acc[mb][nbk][r];
             }
     __syncthreads();
-    {
-        // thread = four consecutive columns of one row, 8 rows per pass: 16-byte stores (the working copy and the P
-        // buffer are 16-byte aligned; the caller's output need not be)
-        const int c4 = (t & 31) * 4, r0 = t >> 5;
+    // thread = four consecutive columns of one row, 8 rows per pass: 16-byte stores (the working copy and the P
+    // buffer are 16-byte aligned; the caller's output need not be)
+    const int c4 = (t & 31) * 4, r0 = t >> 5;
 #pragma unroll 4
+    for (int p = 0; p < 16; ++p) {
+        const int row = r0 + 8 * p;
+        if (row >= nb || c4 >= nb) continue;
+        v4f x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = tri[tri_sym(row, min(c4 + i, nb - 1))];
+        if (last) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (c4 + i < nb) it.Minv[(size_t)(k0 + row) * d + k0 + c4 + i] = -x[i];
+        } else {
+            *(KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4] = x;      // a block that is not last is full
+        }
+        if (!from_S) *(KFAC_AS1 v4f*)&ws.P[row * NB + c4] = -x;    // (columns beyond a ragged block are never read)
+    }
+}
+
+// Pivot block `step` of every matrix of the batch, read from the working copy.
+// from_S: single-block matrices: read S + lambda I and write the caller's output directly.
+__global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int from_S) {
+    __shared__ __attribute__((aligned(16))) float lds[PIV_LDS_FLOATS];
+    const int m = blockIdx.x;
+    const Item it = get_item(b, m);
+    const int d = it.dim;
+    const int k0 = step * NB;
+    const int nb = min(NB, d - k0);
+    const bool last = k0 + NB >= d;
+    const int t = threadIdx.x;
+    const WsView ws = ws_view(it.ws, d);
+
+    // ---- load: lower triangle, row-wise.  All loads are issued before the first LDS store so that the block costs
+    //      one memory round trip, not one per row group ----
+    {
+        const int c4 = (t & 31) * 4, r0 = t >> 5;        // 8 rows x 32 float4 per pass, 16 passes
+        const bool vec_ok = !from_S;                     // the padded working copy is 16-byte aligned, S need not be
+        v4f v[16];
+#pragma unroll
         for (int p = 0; p < 16; ++p) {
             const int row = r0 + 8 * p;
-            if (row >= nb || c4 >= nb) continue;
-            v4f x;
+            v4f x = {0.f, 0.f, 0.f, 0.f};
+            if (row < nb && c4 <= row) {
+                if (vec_ok) {
+                    x = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4];
+                } else {
+                    const gfloat* src = it.S + (size_t)(k0 + row) * d + k0 + c4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int c = min(c4 + i, nb - 1);
-                x[i] = sD[max(row, c) * (NB + 1) + min(row, c)];
+                    for (int i = 0; i < 4; ++i)
+                        if (c4 + i <= row) x[i] = src[i] + (c4 + i == row ? it.damping : 0.f);
+                }
             }
-            if (last) {
+            v[p] = x;
+        }
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (c4 + i < nb) it.Minv[(size_t)(k0 + row) * d + k0 + c4 + i] = -x[i];
-            } else {
-                *(KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + row) * ws.ldw + k0 + c4] = x;      // a block that is not last is full
-            }
-            if (!from_S) *(KFAC_AS1 v4f*)&ws.P[row * NB + c4] = -x;    // (columns beyond a ragged block are never read)
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + 8 * p;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (row < nb && c4 + i <= row) lds[tri_at(row, c4 + i)] = v[p][i];
         }
     }
+    __syncthreads();
+    v16f acc[2][2];
+    pivot_fill(acc, lds, nb);
+    const int f = pivot_sweep(acc, nb, lds);
+    if (t == 0 && it.info) {
+        if (from_S) *it.info = f;                                       // single-block matrix: this is its only kernel
+        else if (f != 0) atomicCAS((int*)it.info, 0, k0 + f);           // keep the first failing minor
+    }
+    pivot_write(acc, lds, it, ws, k0, nb, last, from_S != 0);
 }
 
 // T = U . P for every 128-row slab of block column k; U is copied aside for the update.  Slabs below the pivot
@@ -645,7 +670,11 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
 // the accumulators start as the tile's old values (fetched straight into MFMA register layout: register r of a
 // 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated product is added, and the result is
 // stored from the registers: nothing is staged in LDS.
-__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfloat* __restrict__ U, unsigned char* __restrict__ lds) {
+// STORE = false: the new values stay in acc (valid where the tile has rows and columns; the quadrant above the
+// diagonal of a diagonal tile is not computed) and nothing is written.
+template <bool STORE = true>
+__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfloat* __restrict__ U, unsigned char* __restrict__ lds,
+                                                      TileAcc& acc) {
     [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, h = lane >> 5;
@@ -659,7 +688,6 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfl
         colok[nbk] = !dead && c.j0 + wn * 64 + nbk * 32 < c.ldw;
         wq[nbk] = wtile + (size_t)(wm * 64 + 4 * h) * c.ldw + wn * 64 + nbk * 32 + lm;
     }
-    TileAcc acc;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -672,16 +700,52 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfl
     TR(1);
     tile_mma_nt_split<3, true, NB / SPLIT_KS>(c.T + (size_t)c.i0 * NB, NB, NB, U + (size_t)c.j0 * NB, NB, NB, NB, lds, acc, c.diag);
     TR(3);
+    if constexpr (STORE) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                    if (colok[nbk] && dr < rows_left) wq[nbk][(size_t)dr * c.ldw] = acc.c[mb][nbk][r];
+                }
+    }
+    TR(5);
+}
+
+// Look-ahead: the diagonal tile that is the next step's pivot block is updated by a workgroup of its own, which
+// keeps the new values in registers and inverts the block at once (the pivot sweep is the longest link of the chain
+// pivot -> panel -> update; here it runs beside the update of all other tiles instead of after it).
+__device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* __restrict__ lds) {
+    const int d = it.dim, kn = step + 1;
+    const WsView ws = ws_view(it.ws, d);
+    const int k0 = kn * NB, nb = min(NB, d - k0);
+    UpdCtx c;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T; c.out = it.Minv;
+    c.d = d;
+    c.i0 = c.j0 = k0;
+    c.irows = c.jrows = nb;
+    c.nb = NB;
+    c.diag = true;
+    TileAcc acc;
+    upd_regular_mid_split<false>(c, ws.U, (unsigned char*)lds, acc);
+    __syncthreads();                                     // the product's LDS stages are free
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int nbk = 0; nbk < 2; ++nbk)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
-                if (colok[nbk] && dr < rows_left) wq[nbk][(size_t)dr * c.ldw] = acc.c[mb][nbk][r];
+                const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
+                if (row >= col && row < nb) lds[tri_at(row, col)] = acc.c[mb][nbk][r];
             }
-    TR(5);
+    __syncthreads();
+    pivot_fill(acc.c, lds, nb);
+    const int f = pivot_sweep(acc.c, nb, lds);
+    if (t == 0 && it.info && f != 0) atomicCAS((int*)it.info, 0, k0 + f);
+    pivot_write(acc.c, lds, it, ws, k0, nb, k0 + NB >= d, false);
 }
 
 // column tile (from_rows = true): new[a][c] = T[(i0 + a)][c];  row tile: new[a][c] = T[(j0 + c)][a]
@@ -730,17 +794,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     // Workgroups go to the 8 XCDs round-robin (id % 8) and each XCD has an L2 of its own.  XCD x therefore takes the
     // x-th contiguous eighth of the tile list (matrix by matrix, row-major over the lower triangle): tiles that
     // share a T panel (same block row) and mostly the same U panels run on the same L2 instead of all eight.
+    // The first workgroups (one per matrix, padded to a multiple of 8 so that the others keep their XCD) take the
+    // next step's pivot block; they are dispatched first and run the longest.
+    const int npiv = (b.count + 7) & ~7;
+    if ((int)blockIdx.x < npiv) {
+        if ((int)blockIdx.x >= b.count) return;
+        const Item it = get_item(b, blockIdx.x);
+        if (nblk_of(it.dim) > step + 1) upd_next_pivot(it, step, lds);
+        return;
+    }
+    const unsigned bx = blockIdx.x - npiv;
     const int total = b.prefix[b.count];
     const int per_xcd = (total + 7) >> 3;
-    const int lin = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || lin >= total) return;
+    const int lin = (int)(bx & 7) * per_xcd + (int)(bx >> 3);
+    if ((int)(bx >> 3) >= per_xcd || lin >= total) return;
     int m, tile;
     locate(b, lin, m, tile);
     const Item it = get_item(b, m);
     int I, J;
     tri_decode(tile, I, J);
     const int kb = step;
-    if (I == kb && J == kb) return;             // the pivot block itself was written by inv_pivot_kernel
+    if (I == J && (I == kb || I == kb + 1)) return;     // this step's pivot block and the next one's are written elsewhere
     const bool last = nblk_of(it.dim) == step + 1;      // uniform per workgroup
     const WsView ws = ws_view(it.ws, it.dim);
     UpdCtx c;
@@ -752,7 +826,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     c.diag = I == J;
     if (I != kb && J != kb) {
         if (last) upd_regular<true>(c, ws.U, lds);
-        else upd_regular_mid_split(c, ws.U, (unsigned char*)lds);
+        else { TileAcc acc; upd_regular_mid_split(c, ws.U, (unsigned char*)lds, acc); }
     } else if (last) {
         upd_panel<true>(c, J == kb, lds);
     } else {
@@ -800,12 +874,12 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
         while (active < n_multi && nblk_of(h[active].dim) > step) ++active;
         if (active == 0) break;
         b.count = active;
-        KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);
+        if (step == 0) KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);   // later ones: by the update
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
         KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
         b.count = active;
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(b.prefix[active])), dim3(256), stream, b, step);
+        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(active) + xcd_grid(b.prefix[active])), dim3(256), stream, b, step);
     }
     return KFAC_OK;
 }

@@ -48,11 +48,13 @@ def kernel_work(net: kstep.KfacNetworkStep):
                  sum(kstep.factor_flops(s.R, s.d_G) for s in shapes))
     w = {
         # all steps of all matrices in one kernel; a matrix's last step (short product, dense mirrored output) is a
-        # small part of it
-        "inv_update_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_update_flops(d) for d in dims)),
+        # small part of it; it also inverts the next step's pivot block (fp32 matrix cores) beside the update
+        "inv_update_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s",
+                              sum(kstep.inverse_update_flops(d) + kstep.inverse_pivot_flops(d) - kstep.inverse_first_pivot_flops(d)
+                                  for d in dims)),
         # latency-bound helpers of the sweep (one workgroup per matrix / per 128-row slab): block inverses of nb^3 flops,
         # panel products of 2 d nb^2
-        "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_pivot_flops(d) for d in dims)),
+        "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_first_pivot_flops(d) for d in dims)),
         "inv_panel_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",

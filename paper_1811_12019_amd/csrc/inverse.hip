@@ -424,8 +424,15 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
 
 // T = U . P for every 128-row slab of block column k; U is copied aside for the update.  Slabs below the pivot
 // block read the column block itself; slabs above it read block row k transposed.
+// Full pivot block (every step but a matrix's last): the slab is first copied to U (through an LDS transpose for the
+// slabs above the pivot), all 64 KB in flight at once, and the product then runs on the bf16 matrix cores with both
+// operands split three ways, reading the copy.  Ragged pivot block: fp32 matrix cores, operands guarded.
+constexpr int PANEL_TLD = NB + 1;          // LDS row stride of the transpose stage
+constexpr int PANEL_LDS_FLOATS = NB * PANEL_TLD;
+static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
+
 __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
-    __shared__ float lds[GEMM_LDS_FLOATS];
+    __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
     int m, slab;
     locate(b, blockIdx.x, m, slab);
     const Item it = get_item(b, m);
@@ -436,14 +443,53 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
     const int r0 = slab * NB;
     const int rows = min(NB, d - r0);
     const WsView ws = ws_view(it.ws, d);
+    gfloat* __restrict__ Uc = ws.U + (size_t)r0 * NB;
+    const int t = threadIdx.x;
     TileAcc acc;
-    if (slab > step)
-        tile_mma_nt<false>(ws.W + (size_t)r0 * ws.ldw + k0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc,
-                           ws.U + (size_t)r0 * NB, NB);
-    else
-        tile_mma_nt<true>(ws.W + (size_t)k0 * ws.ldw + r0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc,
-                          ws.U + (size_t)r0 * NB, NB);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    if (nb == NB) {
+        const int c4 = (t & 31) * 4, rr = t >> 5;            // 8 rows x 32 float4 per pass, 16 passes
+        v4f v[16];
+        if (slab > step) {
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const int row = rr + 8 * p;
+                v4f x = {0.f, 0.f, 0.f, 0.f};
+                if (row < rows) x = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(r0 + row) * ws.ldw + k0 + c4];
+                v[p] = x;
+            }
+#pragma unroll
+            for (int p = 0; p < 16; ++p) *(KFAC_AS1 v4f*)&Uc[(size_t)(rr + 8 * p) * NB + c4] = v[p];   // rows past the end: zero
+        } else {
+            // element (a, k) of the slab is W[k0 + k][r0 + a]; a slab above the pivot has all its 128 rows
+#pragma unroll
+            for (int p = 0; p < 16; ++p)
+                v[p] = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + rr + 8 * p) * ws.ldw + r0 + c4];
+#pragma unroll
+            for (int p = 0; p < 16; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds[(c4 + i) * PANEL_TLD + rr + 8 * p] = v[p][i];
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const float* src = &lds[(rr + 8 * p) * PANEL_TLD + c4];
+                *(KFAC_AS1 v4f*)&Uc[(size_t)(rr + 8 * p) * NB + c4] = v4f{src[0], src[1], src[2], src[3]};
+            }
+        }
+        __threadfence_block();
+        __syncthreads();                       // the copy is visible to the whole workgroup; the LDS stage is free
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = 0.f;
+        tile_mma_nt_split<3, false, NB / SPLIT_KS>(Uc, NB, NB, ws.P, NB, NB, NB, (unsigned char*)lds, acc);
+    } else if (slab > step) {
+        tile_mma_nt<false>(ws.W + (size_t)r0 * ws.ldw + k0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc, Uc, NB);
+    } else {
+        tile_mma_nt<true>(ws.W + (size_t)k0 * ws.ldw + r0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc, Uc, NB);
+    }
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -455,9 +501,9 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
             }
     // the update streams whole 16-float slabs of T and U: keep the columns beyond a ragged block at zero
     if (nb < NB) {
-        for (int e = threadIdx.x; e < rows * NB; e += 256) {
+        for (int e = t; e < rows * NB; e += 256) {
             const int row = e >> 7, col = e & (NB - 1);
-            if (col >= nb) ws.U[(size_t)(r0 + row) * NB + col] = 0.f;
+            if (col >= nb) Uc[(size_t)row * NB + col] = 0.f;
         }
     }
 }

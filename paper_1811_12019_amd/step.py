@@ -206,6 +206,12 @@ def inverse_pivot_flops(dim: int) -> float:
     return total
 
 
+def inverse_first_pivot_flops(dim: int) -> float:
+    """The first pivot block's share of inverse_pivot_flops: the only one inverted by a launch of its own (the later
+    ones are inverted inside the update launch of the step before)."""
+    return float(min(INVERSE_BLOCK, dim)) ** 3
+
+
 def inverse_panel_flops(dim: int) -> float:
     """Flops of the panel products T = W_:k P of the blocked sweep (every row outside the pivot block)."""
     if dim <= INVERSE_BLOCK:

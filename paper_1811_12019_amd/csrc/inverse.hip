@@ -82,13 +82,21 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
 
 static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }
 static inline __host__ __device__ int ldw_of(int dim) { return (dim + 31) / 32 * 32; }
+// Steps are taken in pairs (k even, k + 1) while neither is the matrix's last: the update launch of step k then
+// touches only the tiles that step k + 1's pivot and panel need (block row / column k + 1), and the launch of step
+// k + 1 applies both steps' rank-128 updates to all other tiles in one pass over the matrix.
+static inline __host__ __device__ bool pair_mode(int dim, int step) { return nblk_of(dim) > (step & ~1) + 2; }
+static inline __host__ __device__ int update_tiles(int dim, int step) {
+    const int n = nblk_of(dim);
+    return (pair_mode(dim, step) && !(step & 1)) ? n : n * (n + 1) / 2;
+}
 
 struct WsView {
-    gfloat* W;   // dim x ldw : working copy, lower triangle maintained
+    gfloat* W;      // dim x ldw : working copy, lower triangle maintained
     int ldw;
-    gfloat* U;   // d_pad x NB : copy of block column k before the step (all rows, assembled from both triangles)
-    gfloat* T;   // d_pad x NB : U . P
-    gfloat* P;   // NB x NB    : inverse of the pivot block
+    gfloat* U[2];   // d_pad x NB : copy of block column k before step k (all rows, assembled from both triangles)
+    gfloat* T[2];   // d_pad x NB : U . P                                        ([k & 1]: two steps' panels coexist)
+    gfloat* P;      // NB x NB    : inverse of the pivot block
 };
 
 __device__ inline WsView ws_view(gfloat* ws, int dim) {
@@ -96,9 +104,11 @@ __device__ inline WsView ws_view(gfloat* ws, int dim) {
     WsView v;
     v.ldw = ldw_of(dim);
     v.W = ws;
-    v.U = v.W + d_pad * v.ldw;
-    v.T = v.U + d_pad * NB;
-    v.P = v.T + d_pad * NB;
+    v.U[0] = v.W + d_pad * v.ldw;
+    v.T[0] = v.U[0] + d_pad * NB;
+    v.U[1] = v.T[0] + d_pad * NB;
+    v.T[1] = v.U[1] + d_pad * NB;
+    v.P = v.T[1] + d_pad * NB;
     return v;
 }
 
@@ -443,7 +453,8 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
     const int r0 = slab * NB;
     const int rows = min(NB, d - r0);
     const WsView ws = ws_view(it.ws, d);
-    gfloat* __restrict__ Uc = ws.U + (size_t)r0 * NB;
+    gfloat* __restrict__ Uc = ws.U[step & 1] + (size_t)r0 * NB;
+    gfloat* __restrict__ Tc = ws.T[step & 1] + (size_t)r0 * NB;
     const int t = threadIdx.x;
     TileAcc acc;
     if (nb == NB) {
@@ -497,7 +508,7 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                if (row < rows) ws.T[(size_t)(r0 + row) * NB + col] = col < nb ? acc.c[mb][nbk][r] : 0.f;
+                if (row < rows) Tc[(size_t)row * NB + col] = col < nb ? acc.c[mb][nbk][r] : 0.f;
             }
     // the update streams whole 16-float slabs of T and U: keep the columns beyond a ragged block at zero
     if (nb < NB) {
@@ -710,16 +721,24 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
     }
 }
 
-// Regular tile of a step that is not the matrix's last one: new = old - T_I U_J^T goes back into the working copy.
-// Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot block is
-// full (K = 128).  The product runs on the bf16 matrix cores with both operands split three ways (gemm_split.h):
-// the accumulators start as the tile's old values (fetched straight into MFMA register layout: register r of a
-// 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated product is added, and the result is
-// stored from the registers: nothing is staged in LDS.
-// STORE = false: the new values stay in acc (valid where the tile has rows and columns; the quadrant above the
-// diagonal of a diagonal tile is not computed) and nothing is written.
+// Where a tile's old values come from: element (a, c) of the tile is base[a * rs + c * cs].
+struct OldSrc {
+    const gfloat* base;
+    int rs, cs;
+};
+
+// Regular tile of a step that is not the matrix's last one: new = old - A0 B0^T (- A1 B1^T) goes back into the working
+// copy.  Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot
+// blocks are full (K = 128 per product).  The products run on the bf16 matrix cores with both operands split three
+// ways (gemm_split.h): the accumulators start as the tile's old values (fetched straight into MFMA register layout:
+// register r of a 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated products are added,
+// and the result is stored from the registers: nothing is staged in LDS.
+// A1 == nullptr: one product.  STORE = false: the new values stay in acc (valid where the tile has rows and columns;
+// the quadrant above the diagonal of a diagonal tile is not computed) and nothing is written.
 template <bool STORE = true>
-__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfloat* __restrict__ U, unsigned char* __restrict__ lds,
+__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const OldSrc& o, const gfloat* __restrict__ A0,
+                                                      const gfloat* __restrict__ B0, const gfloat* __restrict__ A1,
+                                                      const gfloat* __restrict__ B1, unsigned char* __restrict__ lds,
                                                       TileAcc& acc) {
     [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
@@ -729,10 +748,12 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfl
     const int rows_left = c.irows - wm * 64 - 4 * h;     // tile rows from the lane's first row on
     bool colok[2];
     gfloat* wq[2];
+    const gfloat* oq[2];
 #pragma unroll
     for (int nbk = 0; nbk < 2; ++nbk) {
         colok[nbk] = !dead && c.j0 + wn * 64 + nbk * 32 < c.ldw;
         wq[nbk] = wtile + (size_t)(wm * 64 + 4 * h) * c.ldw + wn * 64 + nbk * 32 + lm;
+        oq[nbk] = o.base + (wm * 64 + 4 * h) * o.rs + (wn * 64 + nbk * 32 + lm) * o.cs;
     }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -741,10 +762,14 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const gfl
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
-                acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? wq[nbk][(size_t)dr * c.ldw] : 0.f;
+                acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? oq[nbk][dr * o.rs] : 0.f;
             }
     TR(1);
-    tile_mma_nt_split<3, true, NB / SPLIT_KS>(c.T + (size_t)c.i0 * NB, NB, NB, U + (size_t)c.j0 * NB, NB, NB, NB, lds, acc, c.diag);
+    tile_mma_nt_split<3, true, NB / SPLIT_KS>(A0, NB, NB, B0, NB, NB, NB, lds, acc, c.diag);
+    if (A1) {                                            // uniform
+        __syncthreads();                                 // the first product's last stage has been read
+        tile_mma_nt_split<3, true, NB / SPLIT_KS>(A1, NB, NB, B1, NB, NB, NB, lds, acc, c.diag);
+    }
     TR(3);
     if constexpr (STORE) {
 #pragma unroll
@@ -768,14 +793,19 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     const WsView ws = ws_view(it.ws, d);
     const int k0 = kn * NB, nb = min(NB, d - k0);
     UpdCtx c;
-    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T; c.out = it.Minv;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T[step & 1]; c.out = it.Minv;
     c.d = d;
     c.i0 = c.j0 = k0;
     c.irows = c.jrows = nb;
     c.nb = NB;
     c.diag = true;
     TileAcc acc;
-    upd_regular_mid_split<false>(c, ws.U, (unsigned char*)lds, acc);
+    const OldSrc o = {ws.W + (size_t)k0 * ws.ldw + k0, ws.ldw, 1};
+    const size_t po = (size_t)k0 * NB;                   // the block's rows in the panels
+    const int cur = step & 1;
+    const bool two = pair_mode(d, step) && cur;          // second step of a pair: the block has seen neither update yet
+    upd_regular_mid_split<false>(c, o, ws.T[two ? 0 : cur] + po, ws.U[two ? 0 : cur] + po, two ? ws.T[1] + po : nullptr,
+                                 two ? ws.U[1] + po : nullptr, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -857,27 +887,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     int m, tile;
     locate(b, lin, m, tile);
     const Item it = get_item(b, m);
-    int I, J;
-    tri_decode(tile, I, J);
+    const int nblk = nblk_of(it.dim);
     const int kb = step;
+    const bool pm = pair_mode(it.dim, step);
+    const bool narrow = pm && !(step & 1), wide = pm && (step & 1);
+    int I, J;
+    if (narrow) {                               // only block row / column kb + 1: (kb+1, 0..kb+1), (kb+2.., kb+1)
+        if (tile <= kb + 1) { I = kb + 1; J = tile; } else { I = tile; J = kb + 1; }
+    } else {
+        tri_decode(tile, I, J);
+    }
     if (I == J && (I == kb || I == kb + 1)) return;     // this step's pivot block and the next one's are written elsewhere
-    const bool last = nblk_of(it.dim) == step + 1;      // uniform per workgroup
+    const bool last = nblk == step + 1;                 // uniform per workgroup
     const WsView ws = ws_view(it.ws, it.dim);
+    const int cur = step & 1;
     UpdCtx c;
-    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T; c.out = it.Minv;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T[cur]; c.out = it.Minv;
     c.d = it.dim;
     c.i0 = I * NB; c.j0 = J * NB;
     c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
     c.nb = min(NB, c.d - step * NB);
     c.diag = I == J;
-    if (I != kb && J != kb) {
-        if (last) upd_regular<true>(c, ws.U, lds);
-        else { TileAcc acc; upd_regular_mid_split(c, ws.U, (unsigned char*)lds, acc); }
-    } else if (last) {
-        upd_panel<true>(c, J == kb, lds);
-    } else {
-        upd_panel<false>(c, J == kb, lds);
+    if (J == kb || I == kb) {                           // block column / row kb becomes the panel
+        if (last) upd_panel<true>(c, J == kb, lds);
+        else upd_panel<false>(c, J == kb, lds);
+        return;
     }
+    if (last) { upd_regular<true>(c, ws.U[cur], lds); return; }
+    TileAcc acc;
+    const gfloat *Ti = ws.T[cur] + (size_t)c.i0 * NB, *Uj = ws.U[cur] + (size_t)c.j0 * NB;
+    // One step: new = old - T_I U_J^T.  Second step of a pair (steps k = kb - 1 and kb): tiles outside block rows /
+    // columns kb have not seen step k yet.
+    OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
+    const gfloat *A0 = Ti, *B0 = Uj, *A1 = nullptr, *B1 = nullptr;
+    const int k = kb - 1;
+    if (wide && !(I == k && J == k)) {                  // (block (k, k) is -P_k, written by the pivot code)
+        if (J == k) {                                   // block column k: step k would have stored T_I (its panel)
+            o = OldSrc{ws.T[cur ^ 1] + (size_t)c.i0 * NB, NB, 1};
+        } else if (I == k) {                            // block row k: step k would have stored T_J transposed
+            o = OldSrc{ws.T[cur ^ 1] + (size_t)c.j0 * NB, 1, NB};
+        } else {                                        // both steps' updates in one pass
+            A0 = ws.T[cur ^ 1] + (size_t)c.i0 * NB; B0 = ws.U[cur ^ 1] + (size_t)c.j0 * NB;
+            A1 = Ti; B1 = Uj;
+        }
+    }
+    upd_regular_mid_split(c, o, A0, B0, A1, B1, (unsigned char*)lds, acc);
 }
 
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
@@ -924,7 +978,7 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
         for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
         KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
         b.count = active;
-        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
+        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + update_tiles(h[i].dim, step);
         KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(active) + xcd_grid(b.prefix[active])), dim3(256), stream, b, step);
     }
     return KFAC_OK;
@@ -933,7 +987,7 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
 static size_t ws_bytes_of(int dim) {
     if (nblk_of(dim) == 1) return 256;
     const size_t d_pad = (size_t)nblk_of(dim) * NB;
-    return align_up((d_pad * ldw_of(dim) + 2 * d_pad * NB + (size_t)NB * NB) * sizeof(float), 256);
+    return align_up((d_pad * ldw_of(dim) + 4 * d_pad * NB + (size_t)NB * NB) * sizeof(float), 256);
 }
 
 static bool item_ok(const kfac_inverse_item& it) {

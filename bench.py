@@ -217,7 +217,7 @@ def main():
     stages = stage_times(net)
     # per-kernel durations over `steps` more steps, HIP events around every launch on the launch stream
     # (the inversion groups run back to back here: kernels that share the GPU would stretch each other's events)
-    net.overlap_inversions = False
+    net.overlap_inversions = False          # (also makes step() run stage after stage)
     kb.kfac_kernel_timing_enable(True)
     for _ in range(args.steps):
         net.step()
@@ -264,7 +264,10 @@ def main():
         "dtype": "bf16 factor inputs, f32 accumulate/inverse/precondition", "data": "synthetic",
         "config": {"workload": f"resnet50_kfac_step_all54layers_batch{args.batch}", "per_gpu_batch": args.batch,
                    "layers": len(layers), "decay": 0.95, "gamma": 1e-3, "inverse_every_step": True},
+        # stages run one after the other for the whole network; the timed step() overlaps them (the long inversion
+        # chains of the widest layers start first and everything else runs beside them), so value < their sum
         "stage_ms": {k: round(v, 3) for k, v in stages.items()},
+        "schedule": f"{len(net.waves)} waves" if net.pipelined and net.waves else "stage by stage",
         "factor_tflops": round(fac_flops / (stages["factors"] * 1e-3) / 1e12, 2),
         "factor_frac_of_bf16_mfma_peak": round(fac_flops / (stages["factors"] * 1e-3) / 1e12 / PEAK["mfma_bf16"], 4),
         "roofline": roofline,

@@ -45,88 +45,137 @@ class LayerState:
         self.P = torch.empty((dG, dA), **f32)
 
 
-class KfacNetworkStep:
-    """All layers of a network resident on one GPU; step() = factor builds, running averages,
-    damped inverses (optionally skipped: stale inverses) and preconditioning for every layer."""
+INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
 
-    def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
-                 decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda",
-                 inverse_streams: int = 3):
-        self.decay = decay
-        self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
-        self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
+
+class _Wave:
+    """A subset of the layers with batched-call tables of its own."""
+
+    def __init__(self, layers: List[LayerState], decay, damping: float, n_groups: int, device):
+        self.layers = layers
         builds = []
-        for l in self.layers:
+        for l in layers:
             builds.append((kb.KFAC_OP_FACTOR_A, l.desc, l.act, l.A_new, 0.0))
             builds.append((kb.KFAC_OP_FACTOR_G, l.desc, l.gout, l.G_new, 0.0))
         self.factor_batch = kb.FactorBatch(builds, device=device)
-        self.pre_batch = kb.PrecondBatch([l.G_inv for l in self.layers], [l.A_inv for l in self.layers],
-                                         [l.gradW for l in self.layers], [l.P for l in self.layers], device=device)
-        self.ema_batch = kb.EmaBatch([t for l in self.layers for t in (l.A_run, l.G_run)],
-                                     [t for l in self.layers for t in (l.A_new, l.G_new)])
-        src = []
-        for l in self.layers:
+        self.pre_batch = kb.PrecondBatch([l.G_inv for l in layers], [l.A_inv for l in layers],
+                                         [l.gradW for l in layers], [l.P for l in layers], device=device)
+        self.ema_batch = kb.EmaBatch([t for l in layers for t in (l.A_run, l.G_run)],
+                                     [t for l in layers for t in (l.A_new, l.G_new)])
+        src, dst = [], []
+        for l in layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
-        dst = []
-        for l in self.layers:
             dst += [l.A_inv, l.G_inv]
         # The inversions are independent, so they are dealt (largest first, to the least loaded group, by d^3) into a
-        # few groups that run on streams of their own: the latency-bound pivot/panel kernels of one group then overlap
-        # with the throughput-bound rank-128 updates of the others.
-        n_groups = max(1, min(inverse_streams, len(src)))
+        # few groups that run on streams of their own: the latency-bound pivot / panel kernels of one group then
+        # overlap with the throughput-bound updates of the others.  (Grouping by block count instead, so that a
+        # group's launches are all equally long, measured 2 % slower.)
+        n_groups = max(1, min(n_groups, len(src)))
         order_by_size = sorted(range(len(src)), key=lambda i: -src[i].shape[0])
         groups, load = [[] for _ in range(n_groups)], [0.0] * n_groups
         for i in order_by_size:
             g = load.index(min(load))
             groups[g].append(i)
             load[g] += float(src[i].shape[0]) ** 3
-        self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [self.damping] * len(grp),
+        self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [damping] * len(grp),
                                             device=device)
                             for grp in groups if grp]
-        self.inv_streams = [torch.cuda.Stream(device=device) for _ in self.inv_batches[1:]]
+
+
+class KfacNetworkStep:
+    """All layers of a network resident on one GPU; step() = factor builds, running averages,
+    damped inverses (optionally skipped: stale inverses) and preconditioning for every layer.
+
+    The stage methods (build_factors, update_running, invert, precondition) run one stage for the whole network.
+    step() strings them together when pipelined is False.  By default it works in two waves instead: the inversion of
+    a 4609-wide factor is a chain of ~110 small dependent launches that takes about half of the whole step and leaves
+    most of the GPU idle, so the factors of the layers with a factor of long_dim or more are built first and their
+    inversions started on the side streams at once; the other layers' stages run on the launch stream beside them,
+    and each wave is preconditioned when its inverses are done."""
+
+    def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
+                 decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda",
+                 inverse_streams: int = 3, long_dim: int = 2048):
+        self.decay = decay
+        self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
+        self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
+        self.all = _Wave(self.layers, decay, self.damping, inverse_streams, device)
+        long_ = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) >= long_dim]
+        short = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) < long_dim]
+        self.waves = ([_Wave(long_, decay, self.damping, inverse_streams, device),
+                       _Wave(short, decay, self.damping, 1, device)] if long_ and short else [])
+        self.inv_streams = [torch.cuda.Stream(device=device) for _ in range(max(1, inverse_streams))]
         self.overlap_inversions = True      # False: run the groups one after the other on the caller's stream
+        self.pipelined = True               # False: step() runs stage after stage
 
     # -- stages ------------------------------------------------------------------------------
     def build_factors(self, stream=None):
-        kb.kfac_factor_batched(self.factor_batch, stream)
+        kb.kfac_factor_batched(self.all.factor_batch, stream)
 
     def update_running(self, stream=None):
         if self.decay is None:
             return
-        kb.kfac_ema_batched(self.ema_batch, self.decay, stream)
+        kb.kfac_ema_batched(self.all.ema_batch, self.decay, stream)
 
-    def invert(self, stream=None):
-        main = torch.cuda.current_stream() if stream is None else stream
-        if len(self.inv_batches) == 1 or not self.overlap_inversions:
-            for batch in self.inv_batches:
-                kb.kfac_damped_inverse_batched(batch, main)
-            return
+    @staticmethod
+    def _fork(batches, sides, main):
+        """batches[i] on sides[i], after what `main` holds now; returns the events to join on."""
         fork = torch.cuda.Event()
         fork.record(main)
         joins = []
-        for batch, side in zip(self.inv_batches[1:], self.inv_streams):
+        for batch, side in zip(batches, sides):
             side.wait_event(fork)
             kb.kfac_damped_inverse_batched(batch, side)
             done = torch.cuda.Event()
             done.record(side)
             joins.append(done)
-        kb.kfac_damped_inverse_batched(self.inv_batches[0], main)
+        return joins
+
+    def invert(self, stream=None):
+        main = torch.cuda.current_stream() if stream is None else stream
+        batches = self.all.inv_batches
+        if not self.overlap_inversions or len(batches) == 1:
+            for batch in batches:
+                kb.kfac_damped_inverse_batched(batch, main)
+            return
+        joins = self._fork(batches, self.inv_streams, main)
         for done in joins:
             main.wait_event(done)
 
     def inverse_info(self) -> torch.Tensor:
         """Status words of all inversions (0 = positive definite)."""
-        return torch.cat([b.info for b in self.inv_batches])
+        sets = self.waves if self._use_waves(True) else [self.all]
+        return torch.cat([b.info for w in sets for b in w.inv_batches])
 
     def precondition(self, stream=None):
-        kb.kfac_precondition_batched(self.pre_batch, stream)
+        kb.kfac_precondition_batched(self.all.pre_batch, stream)
+
+    def _use_waves(self, refresh_inverse: bool) -> bool:
+        return bool(self.pipelined and self.overlap_inversions and refresh_inverse and self.waves)
 
     def step(self, refresh_inverse: bool = True, stream=None):
-        self.build_factors(stream)
-        self.update_running(stream)
-        if refresh_inverse:
-            self.invert(stream)
-        self.precondition(stream)
+        if not self._use_waves(refresh_inverse):
+            self.build_factors(stream)
+            self.update_running(stream)
+            if refresh_inverse:
+                self.invert(stream)
+            self.precondition(stream)
+            return
+        main = torch.cuda.current_stream() if stream is None else stream
+        lw, sw = self.waves
+        kb.kfac_factor_batched(lw.factor_batch, main)
+        if self.decay is not None:
+            kb.kfac_ema_batched(lw.ema_batch, self.decay, main)
+        joins = self._fork(lw.inv_batches, self.inv_streams, main)
+        kb.kfac_factor_batched(sw.factor_batch, main)
+        if self.decay is not None:
+            kb.kfac_ema_batched(sw.ema_batch, self.decay, main)
+        for batch in sw.inv_batches:
+            kb.kfac_damped_inverse_batched(batch, main)
+        kb.kfac_precondition_batched(sw.pre_batch, main)
+        for done in joins:
+            main.wait_event(done)
+        kb.kfac_precondition_batched(lw.pre_batch, main)
 
     def reset_running(self):
         for l in self.layers:
@@ -170,8 +219,6 @@ def inverse_flops(dim: int) -> float:
 def precondition_flops(dG: int, dA: int) -> float:
     return 2.0 * dG * dG * dA + 2.0 * dG * dA * dA
 
-
-INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
 
 
 def inverse_update_flops_split(dim: int):

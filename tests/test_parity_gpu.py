@@ -622,14 +622,19 @@ NET_LAYERS = [
 END_TO_END_TOL = 2e-3
 
 
-def test_network_step_with_stale_inverses():
+@pytest.mark.parametrize("long_dim", [2048, 140])
+def test_network_step_with_stale_inverses(long_dim):
     """KfacNetworkStep (batched entry points only) over three steps, inverses refreshed on steps 0 and 2 only:
-    every stage of every layer against the oracle, stale inverses untouched on step 1."""
+    every stage of every layer against the oracle, stale inverses untouched on step 1.  long_dim = 140 makes two
+    waves (the four layers with a factor of 145 to 361, the two others); the first is inverted on side streams beside
+    the second's stages: the schedule the benchmark times.  The default threshold leaves this small
+    network in one wave, stage after stage."""
     from paper_1811_12019_amd import step as kstep
     decay, gamma = 0.95, 1e-3
     lam = ko.factor_damping(gamma)
     net = kstep.KfacNetworkStep(NET_LAYERS, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=decay, gamma=gamma,
-                                seed=3, device=DEV, inverse_streams=2)
+                                seed=3, device=DEV, inverse_streams=2, long_dim=long_dim)
+    assert len(net.waves) == (2 if long_dim == 140 else 0)
     f64 = lambda t: t.detach().cpu().numpy().astype(np.float64)
     nchw = lambda t: t.float().permute(0, 3, 1, 2).cpu().numpy().astype(np.float64)
     chain = [dict(A_run=np.eye(l.shape.d_A), G_run=np.eye(l.shape.d_G)) for l in net.layers]     # all-float64 chain

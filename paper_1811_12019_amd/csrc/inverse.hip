@@ -83,12 +83,13 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
 static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }
 static inline __host__ __device__ int ldw_of(int dim) { return (dim + 31) / 32 * 32; }
 // Steps are taken in pairs (k even, k + 1) while neither is the matrix's last: the update launch of step k then
-// touches only the tiles that step k + 1's pivot and panel need (block row / column k + 1), and the launch of step
-// k + 1 applies both steps' rank-128 updates to all other tiles in one pass over the matrix.
+// touches only the tiles that step k + 1's pivot and panel need (block row / column k + 1) and the pivot block after
+// next, and the launch of step k + 1 applies both steps' rank-128 updates to all other tiles in one pass over the
+// matrix.
 static inline __host__ __device__ bool pair_mode(int dim, int step) { return nblk_of(dim) > (step & ~1) + 2; }
 static inline __host__ __device__ int update_tiles(int dim, int step) {
     const int n = nblk_of(dim);
-    return (pair_mode(dim, step) && !(step & 1)) ? n : n * (n + 1) / 2;
+    return (pair_mode(dim, step) && !(step & 1)) ? n + 1 : n * (n + 1) / 2;
 }
 
 struct WsView {
@@ -223,7 +224,9 @@ __device__ __forceinline__ int tri_at(int r, int c) { return ((r * (r + 1)) >> 1
 __device__ __forceinline__ int tri_sym(int r, int c) { return r >= c ? tri_at(r, c) : tri_at(c, r); }
 
 // D (accumulator layout, all four quadrants) <- the symmetric block whose lower triangle is in tri, bordered by the
-// identity beyond nb.  Ends with a barrier: tri may be overwritten afterwards.
+// identity beyond nb.  HAVE_LOWER: the registers already hold the lower triangle, only the rest is fetched.
+// Ends with a barrier: tri may be overwritten afterwards.
+template <bool HAVE_LOWER = false>
 __device__ __forceinline__ void pivot_fill(v16f (&acc)[2][2], const float* __restrict__ tri, int nb) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -233,7 +236,8 @@ __device__ __forceinline__ void pivot_fill(v16f (&acc)[2][2], const float* __res
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                acc[mb][nbk][r] = (row < nb && col < nb) ? tri[tri_sym(row, col)] : (row == col ? 1.f : 0.f);
+                if (!(row < nb && col < nb)) acc[mb][nbk][r] = row == col ? 1.f : 0.f;
+                else if (!HAVE_LOWER || row < col) acc[mb][nbk][r] = tri[tri_sym(row, col)];
             }
     __syncthreads();
 }
@@ -802,10 +806,8 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     TileAcc acc;
     const OldSrc o = {ws.W + (size_t)k0 * ws.ldw + k0, ws.ldw, 1};
     const size_t po = (size_t)k0 * NB;                   // the block's rows in the panels
-    const int cur = step & 1;
-    const bool two = pair_mode(d, step) && cur;          // second step of a pair: the block has seen neither update yet
-    upd_regular_mid_split<false>(c, o, ws.T[two ? 0 : cur] + po, ws.U[two ? 0 : cur] + po, two ? ws.T[1] + po : nullptr,
-                                 two ? ws.U[1] + po : nullptr, (unsigned char*)lds, acc);
+    const int cur = step & 1;                            // (in a pair's second step the block has seen the first already)
+    upd_regular_mid_split<false>(c, o, ws.T[cur] + po, ws.U[cur] + po, nullptr, nullptr, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -818,7 +820,7 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
                 if (row >= col && row < nb) lds[tri_at(row, col)] = acc.c[mb][nbk][r];
             }
     __syncthreads();
-    pivot_fill(acc.c, lds, nb);
+    pivot_fill<true>(acc.c, lds, nb);
     const int f = pivot_sweep(acc.c, nb, lds);
     if (t == 0 && it.info && f != 0) atomicCAS((int*)it.info, 0, k0 + f);
     pivot_write(acc.c, lds, it, ws, k0, nb, k0 + NB >= d, false);
@@ -892,8 +894,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     const bool pm = pair_mode(it.dim, step);
     const bool narrow = pm && !(step & 1), wide = pm && (step & 1);
     int I, J;
-    if (narrow) {                               // only block row / column kb + 1: (kb+1, 0..kb+1), (kb+2.., kb+1)
-        if (tile <= kb + 1) { I = kb + 1; J = tile; } else { I = tile; J = kb + 1; }
+    if (narrow) {                               // block row / column kb + 1: (kb+1, 0..kb+1), (kb+2.., kb+1); (kb+2, kb+2)
+        if (tile <= kb + 1) { I = kb + 1; J = tile; }
+        else if (tile < nblk) { I = tile; J = kb + 1; }
+        else { I = J = kb + 2; }
     } else {
         tri_decode(tile, I, J);
     }

@@ -440,7 +440,8 @@ def gpu_inverse(S, damping):
     return out.cpu().numpy(), int(info.item())
 
 
-@pytest.mark.parametrize("dim", [1, 2, 16, 64, 65, 128, 129, 148, 257, 300, 513, 640, 1153])
+# (block counts 1 .. 10: matrices that never, sometimes and mostly take their steps in pairs; ragged and full last blocks)
+@pytest.mark.parametrize("dim", [1, 2, 16, 64, 65, 128, 129, 148, 256, 257, 300, 384, 512, 513, 640, 769, 897, 1153])
 def test_damped_inverse_random_spd(dim):
     S = synth.random_spd(dim, seed=3, eig_lo=1e-3, eig_hi=10.0, n_zero=dim // 3)
     lam = float(np.float32(np.sqrt(1e-3)))
@@ -470,7 +471,7 @@ def test_damped_inverse_diagonal_and_identity():
     np.testing.assert_allclose(Minv, np.diag(1 / (np.arange(1, 201) + 0.5)), rtol=0, atol=1e-7)
 
 
-@pytest.mark.parametrize("dim", [40, 300])
+@pytest.mark.parametrize("dim", [40, 300, 700, 1100])
 def test_damped_inverse_reports_not_positive_definite(dim):
     S = np.eye(dim, dtype=np.float32)
     S[dim // 2, dim // 2] = -2.0

@@ -52,10 +52,10 @@ def kernel_work(net: kstep.KfacNetworkStep):
         "inv_update_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s",
                               sum(kstep.inverse_update_flops(d) + kstep.inverse_pivot_flops(d) - kstep.inverse_first_pivot_flops(d)
                                   for d in dims)),
-        # latency-bound helpers of the sweep (one workgroup per matrix / per 128-row slab): block inverses of nb^3 flops,
-        # panel products of 2 d nb^2
+        # latency-bound helpers of the sweep (one workgroup per matrix / per 128-row slab): first-block inverses of nb^3
+        # flops (fp32 matrix cores), panel products of 2 d nb^2 (bf16 matrix cores, operands split three ways)
         "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_first_pivot_flops(d) for d in dims)),
-        "inv_panel_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
+        "inv_panel_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),

@@ -5,13 +5,16 @@
 // starts at i n - i (i - 1) / 2 and the whole has n (n + 1) / 2 elements.
 // All matrices of a call go in one launch (workgroup -> matrix through prefix sums in the kernel arguments).  Packing
 // walks the packed array linearly (aligned 16-byte stores; the sources are runs of matrix rows).  The packed running
-// average works on 64 x 64 tiles (I <= J), one workgroup per tile: a tile row is a contiguous run both in the full
+// average works on 128 x 128 tiles (I <= J), one workgroup per tile: a tile row is a contiguous run both in the full
 // matrix and in the packed array, and the mirrored tile is written row-wise after a transpose through LDS.  HBM bound.
 #include "common.h"
 
 namespace kfac {
 
-constexpr int PK_T = 64;              // tile edge
+#ifndef PK_TILE
+#define PK_TILE 128
+#endif
+constexpr int PK_T = PK_TILE;         // tile edge
 constexpr int PK_MAX = 128;           // matrices per launch (keeps the argument block under 4 KB)
 
 struct PackBatch {
@@ -39,7 +42,7 @@ __device__ __forceinline__ void pk_locate(const PackBatch& b, int& m, int& I, in
 }
 
 // Thread = 4 consecutive columns of one tile row (16-byte accesses at 4-byte alignment: rows of an odd-sized matrix
-// and rows of the packed array start anywhere); 16 tile rows per pass, 4 passes.
+// and rows of the packed array start anywhere); 8 tile rows per pass, 16 passes, the loads of 8 passes in flight.
 __device__ __forceinline__ v4f pk_load4(const gfloat* p, int valid_from, int valid_to) {     // elements [from, to) of 4
     if (valid_from == 0 && valid_to == 4) return *(const KFAC_AS1 v4f_a4*)p;
     v4f v = {0.f, 0.f, 0.f, 0.f};
@@ -97,6 +100,12 @@ __global__ __launch_bounds__(256) void pack_upper_kernel(PackBatch b) {
 }
 
 // running <- decay * running + (1 - decay) * unpack(packed), both triangles of running written, exactly symmetric
+constexpr int PK_TPR = PK_T / 4;            // threads per tile row
+constexpr int PK_RPP = 256 / PK_TPR;        // tile rows per pass
+constexpr int PK_NP = PK_T / PK_RPP;        // passes
+#ifndef PK_GROUP
+#define PK_GROUP 8                          // passes whose loads are in flight together
+#endif
 __global__ __launch_bounds__(256) void ema_packed_kernel(PackBatch b, float decay, float one_minus) {
     __shared__ float tile[PK_T][PK_T + 1];
     int m, I, J;
@@ -104,37 +113,40 @@ __global__ __launch_bounds__(256) void ema_packed_kernel(PackBatch b, float deca
     const int n = b.dim[m];
     gfloat* __restrict__ R = as_global(b.full[m]);
     const gfloat* __restrict__ P = as_global(b.packed[m]);
-    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+    const int c4 = (threadIdx.x % PK_TPR) * 4, r0 = threadIdx.x / PK_TPR;
     const int j = J * PK_T + c4;
-    v4f run[4], fresh[4];
-    int from[4], to[4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int i = I * PK_T + r0 + 16 * p;
-        from[p] = min(4, max(0, i - j));
-        to[p] = i < n ? min(4, max(0, n - j)) : 0;
-        if (from[p] >= to[p]) { from[p] = to[p] = 0; continue; }
-        run[p] = pk_load4(R + (size_t)i * n + j, from[p], to[p]);
-        fresh[p] = pk_load4(P + pk_row_start(i, n) + (j - i), from[p], to[p]);
-    }
+    for (int g = 0; g < PK_NP; g += PK_GROUP) {
+        v4f run[PK_GROUP], fresh[PK_GROUP];
+        int from[PK_GROUP], to[PK_GROUP];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int r = r0 + 16 * p, i = I * PK_T + r;
-        v4f v = {0.f, 0.f, 0.f, 0.f};
-        if (from[p] < to[p]) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = fmaf(decay, run[p][e], one_minus * fresh[p][e]);
-            pk_store4(R + (size_t)i * n + j, v, from[p], to[p]);
+        for (int q = 0; q < PK_GROUP; ++q) {
+            const int i = I * PK_T + r0 + PK_RPP * (g + q);
+            from[q] = min(4, max(0, i - j));
+            to[q] = i < n ? min(4, max(0, n - j)) : 0;
+            if (from[q] >= to[q]) { from[q] = to[q] = 0; continue; }
+            run[q] = pk_load4(R + (size_t)i * n + j, from[q], to[q]);
+            fresh[q] = pk_load4(P + pk_row_start(i, n) + (j - i), from[q], to[q]);
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) tile[r][c4 + e] = v[e];
+        for (int q = 0; q < PK_GROUP; ++q) {
+            const int r = r0 + PK_RPP * (g + q), i = I * PK_T + r;
+            v4f v = {0.f, 0.f, 0.f, 0.f};
+            if (from[q] < to[q]) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = fmaf(decay, run[q][e], one_minus * fresh[q][e]);
+                pk_store4(R + (size_t)i * n + j, v, from[q], to[q]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tile[r][c4 + e] = v[e];
+        }
     }
     __syncthreads();
-    // mirror image: row J*64 + r', columns I*64 + c' <- tile[c'][r'], strictly below the diagonal only
+    // mirror image: row J*T + r', columns I*T + c' <- tile[c'][r'], strictly below the diagonal only
     const int i2 = I * PK_T + c4;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int r = r0 + 16 * p, j2 = J * PK_T + r;
+    for (int p = 0; p < PK_NP; ++p) {
+        const int r = r0 + PK_RPP * p, j2 = J * PK_T + r;
         if (j2 >= n) continue;
         const int hi = min(4, min(n - i2, j2 - i2));             // columns i2 + e < min(n, j2)
         if (hi <= 0) continue;

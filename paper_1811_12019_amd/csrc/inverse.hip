@@ -70,14 +70,14 @@ __device__ __forceinline__ Item get_item(const Batch& b, int m) {
     return it;
 }
 
+// Which matrix workgroup `wg` of a launch belongs to (prefix[m] <= wg < prefix[m + 1]) and its index inside it.
+// Every thread compares one prefix entry and the workgroup counts the matrices that end at or before wg: one vector
+// load and one barrier instead of a binary search of dependent scalar loads (2 us at the start of every workgroup).
+// Must be called by all threads of the workgroup.
 __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& local) {
-    int lo = 0, hi = b.count;   // find m with prefix[m] <= wg < prefix[m+1]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (b.prefix[mid] <= wg) lo = mid; else hi = mid;
-    }
-    m = lo;
-    local = wg - b.prefix[lo];
+    const int t = threadIdx.x;
+    m = __syncthreads_count(t < b.count - 1 && b.prefix[t + 1] <= wg);
+    local = wg - b.prefix[m];
 }
 
 static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }

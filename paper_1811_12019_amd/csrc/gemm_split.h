@@ -165,4 +165,130 @@ __device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, 
     }
 }
 
+// ---- two fp16 pieces ---------------------------------------------------------------------------------------------
+// x = h0 + h1 with h0 = fp16(x), h1 = fp16(x - h0): 11 significant bits each, 22 together, and the three piece
+// products h0 h0 + h0 h1 + h1 h0 (exact in the fp32 accumulator) leave a relative error of ~2^-22 per product: on a
+// par with fp32 for a sum of 128 terms, at half the matrix-core work and two thirds of the LDS traffic of three bf16
+// pieces.  fp16 has a narrow exponent range, so every operand panel comes with a power-of-two scale that brings its
+// largest magnitude to about 1 (smaller entries then lose bits only below 2^-24 of the largest, as in fp32 relative
+// to the panel); the caller scales the accumulators to match (exact) and back afterwards.
+typedef _Float16 v2h_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void split4_h2(const v4f& x, uint2 (&piece)[2]) {
+    v4f rem = x;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const v2f_t lo2 = {rem.x, rem.y}, hi2 = {rem.z, rem.w};
+        const v2h_t a = __builtin_convertvector(lo2, v2h_t), b = __builtin_convertvector(hi2, v2h_t);
+        unsigned ua, ub;
+        __builtin_memcpy(&ua, &a, 4);
+        __builtin_memcpy(&ub, &b, 4);
+        piece[p] = make_uint2(ua, ub);
+        if (p == 0) {
+            const v2f_t la = __builtin_convertvector(a, v2f_t), lb = __builtin_convertvector(b, v2f_t);
+            rem.x -= la.x; rem.y -= la.y; rem.z -= lb.x; rem.w -= lb.y;
+        }
+    }
+}
+
+// Scale (a power of two, as a float) that brings a panel whose largest magnitude is `amax` to at most 1; exponents
+// are kept within +-30 so that products of two scales and their reciprocals stay far from the ends of the fp32 range.
+__device__ __forceinline__ float panel_scale(float amax) {
+    int e = 0;
+    if (amax > 0.f) {
+        (void)frexpf(amax, &e);                        // amax = m 2^e, 0.5 <= m < 1
+        e = max(-30, min(30, e));
+    }
+    return ldexpf(1.0f, -e);
+}
+
+// acc[128 x 128] -= (sa A)(sb B)^T for complete, 16-byte aligned panels of NST * 16 columns (see tile_mma_nt_split with
+// NST > 0): both operands fp32, scaled by sa / sb and split into two fp16 pieces on the fly.
+// pre: acc is multiplied by it first (the caller's scaling of what acc already holds), as late as possible: acc may
+// still be arriving from memory while the first slabs are fetched and split.
+// lds: split_lds_bytes<2>() bytes.  Every wavefront multiplies (no branches), also the quadrant a diagonal tile does
+// not need.
+template <int NST>
+__device__ __forceinline__ void tile_mms_nt_split_h2(const gfloat* __restrict__ A, int lda, float sa,
+                                                     const gfloat* __restrict__ B, int ldb, float sb,
+                                                     unsigned char* __restrict__ lds, TileAcc& acc, float pre) {
+    constexpr int NS = 2;
+    constexpr int BUF = 2 * NS * SPLIT_PLANE;          // bytes per buffer
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    const int lr = t >> 2, kq = t & 3;
+    unsigned w_off[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int row = lr + 64 * p;
+        w_off[p] = (unsigned)(row * 32 + (((kq >> 1) ^ ((row >> 2) & 1)) * 16) + (kq & 1) * 8);
+    }
+    unsigned a_off[2], b_off[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int ra = wm * 64 + q * 32 + lm, rb = wn * 64 + q * 32 + lm;
+        a_off[q] = (unsigned)(ra * 32 + ((h ^ ((ra >> 2) & 1)) * 16));
+        b_off[q] = (unsigned)(rb * 32 + ((h ^ ((rb >> 2) & 1)) * 16) + NS * SPLIT_PLANE);
+    }
+    const float nsa = -sa;
+    v4f ra[2][2], rb[2][2];
+    auto fetch = [&](int k0, v4f (&xa)[2], v4f (&xb)[2]) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = lr + 64 * p;
+            xa[p] = *(const KFAC_AS1 v4f*)(A + (size_t)row * lda + k0 + 4 * kq);
+            xb[p] = *(const KFAC_AS1 v4f*)(B + (size_t)row * ldb + k0 + 4 * kq);
+        }
+    };
+    auto stash = [&](int buf, const v4f (&xa)[2], const v4f (&xb)[2]) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint2 pa[NS], pb[NS];
+            split4_h2(xa[p] * nsa, pa);                // scaled and negated here, not at the fetch
+            split4_h2(xb[p] * sb, pb);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                *(uint2*)(lds + buf * BUF + s * SPLIT_PLANE + w_off[p]) = pa[s];
+                *(uint2*)(lds + buf * BUF + (NS + s) * SPLIT_PLANE + w_off[p]) = pb[s];
+            }
+        }
+    };
+    auto mma = [&](int buf) {
+        uint4 a[2][NS], b[2][NS];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int p = 0; p < NS; ++p) {
+                a[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + a_off[q]);
+                b[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + b_off[q]);
+            }
+        // smallest terms first
+#pragma unroll
+        for (int order = NS - 1; order >= 0; --order)
+#pragma unroll
+            for (int pa = 0; pa <= order; ++pa)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        acc.c[mb][nb] = mfma16<true>(a[mb][pa], b[nb][order - pa], acc.c[mb][nb]);
+    };
+    fetch(0, ra[0], rb[0]);
+    if (NST > 1) fetch(SPLIT_KS, ra[1], rb[1]);
+    stash(0, ra[0], rb[0]);
+    __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc.c[mb][nb] *= pre;
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        if (s + 2 < NST) fetch((s + 2) * SPLIT_KS, ra[s & 1], rb[s & 1]);
+        mma(s & 1);
+        if (s + 1 < NST) stash((s + 1) & 1, ra[(s + 1) & 1], rb[(s + 1) & 1]);
+        __syncthreads();
+    }
+}
+
 }  // namespace kfac

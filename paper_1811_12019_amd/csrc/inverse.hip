@@ -98,6 +98,7 @@ struct WsView {
     gfloat* U[2];   // d_pad x NB : copy of block column k before step k (all rows, assembled from both triangles)
     gfloat* T[2];   // d_pad x NB : U . P                                        ([k & 1]: two steps' panels coexist)
     gfloat* P;      // NB x NB    : inverse of the pivot block
+    gfloat* SC;     // 4 x nblk   : power-of-two scales of the 128-row slabs of T[0], U[0], T[1], U[1] (gemm_split.h)
 };
 
 __device__ inline WsView ws_view(gfloat* ws, int dim) {
@@ -110,6 +111,7 @@ __device__ inline WsView ws_view(gfloat* ws, int dim) {
     v.U[1] = v.T[0] + d_pad * NB;
     v.T[1] = v.U[1] + d_pad * NB;
     v.P = v.T[1] + d_pad * NB;
+    v.SC = v.P + (size_t)NB * NB;
     return v;
 }
 
@@ -445,8 +447,20 @@ constexpr int PANEL_TLD = NB + 1;          // LDS row stride of the transpose st
 constexpr int PANEL_LDS_FLOATS = NB * PANEL_TLD;
 static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
 
+// largest magnitude over the workgroup (every thread gets it); red: 4 floats of LDS
+__device__ __forceinline__ float block_absmax(float x, float* __restrict__ red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    x = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    return x;
+}
+
 __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
+    __shared__ float red[4];
     int m, slab;
     locate(b, blockIdx.x, m, slab);
     const Item it = get_item(b, m);
@@ -490,6 +504,13 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
                 *(KFAC_AS1 v4f*)&Uc[(size_t)(rr + 8 * p) * NB + c4] = v4f{src[0], src[1], src[2], src[3]};
             }
         }
+        float um = 0.f;                        // the slab's scale for the update's fp16 pieces
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) um = fmaxf(um, fabsf(v[p][i]));
+        um = block_absmax(um, red);
+        if (t == 0) ws.SC[((step & 1) * 2 + 1) * nblk_of(d) + slab] = panel_scale(um);
         __threadfence_block();
         __syncthreads();                       // the copy is visible to the whole workgroup; the LDS stage is free
 #pragma unroll
@@ -514,6 +535,17 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
                 int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
                 if (row < rows) Tc[(size_t)row * NB + col] = col < nb ? acc.c[mb][nbk][r] : 0.f;
             }
+    if (nb == NB) {
+        float tm = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tm = fmaxf(tm, fabsf(acc.c[mb][nbk][r]));
+        tm = block_absmax(tm, red);
+        if (t == 0) ws.SC[((step & 1) * 2 + 0) * nblk_of(d) + slab] = panel_scale(tm);
+    }
     // the update streams whole 16-float slabs of T and U: keep the columns beyond a ragged block at zero
     if (nb < NB) {
         for (int e = t; e < rows * NB; e += 256) {
@@ -733,17 +765,22 @@ struct OldSrc {
 
 // Regular tile of a step that is not the matrix's last one: new = old - A0 B0^T (- A1 B1^T) goes back into the working
 // copy.  Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot
-// blocks are full (K = 128 per product).  The products run on the bf16 matrix cores with both operands split three
-// ways (gemm_split.h): the accumulators start as the tile's old values (fetched straight into MFMA register layout:
+// blocks are full (K = 128 per product).  The products run on the fp16 matrix cores with both operands scaled per
+// slab and split two ways (gemm_split.h): the accumulators start as the tile's old values (fetched straight into MFMA register layout:
 // register r of a 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated products are added,
 // and the result is stored from the registers: nothing is staged in LDS.
-// A1 == nullptr: one product.  STORE = false: the new values stay in acc (valid where the tile has rows and columns;
+// p1.A == nullptr: one product.  STORE = false: the new values stay in acc (valid where the tile has rows and columns;
 // the quadrant above the diagonal of a diagonal tile is not computed) and nothing is written.
+// One rank-128 product of a regular tile: T rows (with their slab's scale) and U rows (with theirs).
+struct PanelPair {
+    const gfloat* A;
+    const gfloat* B;
+    float sa, sb;
+};
+
 template <bool STORE = true>
-__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const OldSrc& o, const gfloat* __restrict__ A0,
-                                                      const gfloat* __restrict__ B0, const gfloat* __restrict__ A1,
-                                                      const gfloat* __restrict__ B1, unsigned char* __restrict__ lds,
-                                                      TileAcc& acc) {
+__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const OldSrc& o, const PanelPair& p0,
+                                                      const PanelPair& p1, unsigned char* __restrict__ lds, TileAcc& acc) {
     [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, h = lane >> 5;
@@ -759,6 +796,8 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
         wq[nbk] = wtile + (size_t)(wm * 64 + 4 * h) * c.ldw + wn * 64 + nbk * 32 + lm;
         oq[nbk] = o.base + (wm * 64 + 4 * h) * o.rs + (wn * 64 + nbk * 32 + lm) * o.cs;
     }
+    // the products run on operands scaled by sa, sb (powers of two): the accumulators follow, exactly
+    const float s0 = p0.sa * p0.sb;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -769,11 +808,17 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
                 acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? oq[nbk][dr * o.rs] : 0.f;
             }
     TR(1);
-    tile_mma_nt_split<3, true, NB / SPLIT_KS>(A0, NB, NB, B0, NB, NB, NB, lds, acc, c.diag);
-    if (A1) {                                            // uniform
-        __syncthreads();                                 // the first product's last stage has been read
-        tile_mma_nt_split<3, true, NB / SPLIT_KS>(A1, NB, NB, B1, NB, NB, NB, lds, acc, c.diag);
+    tile_mms_nt_split_h2<NB / SPLIT_KS>(p0.A, NB, p0.sa, p0.B, NB, p0.sb, lds, acc, s0);
+    float back = 1.0f / s0;
+    if (p1.A) {                                          // uniform
+        const float s1 = p1.sa * p1.sb;
+        tile_mms_nt_split_h2<NB / SPLIT_KS>(p1.A, NB, p1.sa, p1.B, NB, p1.sb, lds, acc, s1 * back);
+        back = 1.0f / s1;
     }
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nbk = 0; nbk < 2; ++nbk) acc.c[mb][nbk] *= back;
     TR(3);
     if constexpr (STORE) {
 #pragma unroll
@@ -807,7 +852,10 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     const OldSrc o = {ws.W + (size_t)k0 * ws.ldw + k0, ws.ldw, 1};
     const size_t po = (size_t)k0 * NB;                   // the block's rows in the panels
     const int cur = step & 1;                            // (in a pair's second step the block has seen the first already)
-    upd_regular_mid_split<false>(c, o, ws.T[cur] + po, ws.U[cur] + po, nullptr, nullptr, (unsigned char*)lds, acc);
+    const int nblk = nblk_of(d);
+    const PanelPair p0 = {ws.T[cur] + po, ws.U[cur] + po, ws.SC[(cur * 2 + 0) * nblk + kn], ws.SC[(cur * 2 + 1) * nblk + kn]};
+    const PanelPair none = {nullptr, nullptr, 1.f, 1.f};
+    upd_regular_mid_split<false>(c, o, p0, none, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -919,11 +967,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     }
     if (last) { upd_regular<true>(c, ws.U[cur], lds); return; }
     TileAcc acc;
-    const gfloat *Ti = ws.T[cur] + (size_t)c.i0 * NB, *Uj = ws.U[cur] + (size_t)c.j0 * NB;
+    auto pair_of = [&](int buf) {
+        return PanelPair{ws.T[buf] + (size_t)c.i0 * NB, ws.U[buf] + (size_t)c.j0 * NB, ws.SC[(buf * 2 + 0) * nblk + I],
+                         ws.SC[(buf * 2 + 1) * nblk + J]};
+    };
     // One step: new = old - T_I U_J^T.  Second step of a pair (steps k = kb - 1 and kb): tiles outside block rows /
     // columns kb have not seen step k yet.
     OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
-    const gfloat *A0 = Ti, *B0 = Uj, *A1 = nullptr, *B1 = nullptr;
+    PanelPair p0 = pair_of(cur), p1 = {nullptr, nullptr, 1.f, 1.f};
     const int k = kb - 1;
     if (wide && !(I == k && J == k)) {                  // (block (k, k) is -P_k, written by the pivot code)
         if (J == k) {                                   // block column k: step k would have stored T_I (its panel)
@@ -931,11 +982,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
         } else if (I == k) {                            // block row k: step k would have stored T_J transposed
             o = OldSrc{ws.T[cur ^ 1] + (size_t)c.j0 * NB, 1, NB};
         } else {                                        // both steps' updates in one pass
-            A0 = ws.T[cur ^ 1] + (size_t)c.i0 * NB; B0 = ws.U[cur ^ 1] + (size_t)c.j0 * NB;
-            A1 = Ti; B1 = Uj;
+            p1 = p0;
+            p0 = pair_of(cur ^ 1);
         }
     }
-    upd_regular_mid_split(c, o, A0, B0, A1, B1, (unsigned char*)lds, acc);
+    upd_regular_mid_split(c, o, p0, p1, (unsigned char*)lds, acc);
 }
 
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
@@ -991,7 +1042,7 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
 static size_t ws_bytes_of(int dim) {
     if (nblk_of(dim) == 1) return 256;
     const size_t d_pad = (size_t)nblk_of(dim) * NB;
-    return align_up((d_pad * ldw_of(dim) + 4 * d_pad * NB + (size_t)NB * NB) * sizeof(float), 256);
+    return align_up((d_pad * ldw_of(dim) + 4 * d_pad * NB + (size_t)NB * NB + 4 * (size_t)nblk_of(dim)) * sizeof(float), 256);
 }
 
 static bool item_ok(const kfac_inverse_item& it) {

@@ -28,10 +28,12 @@ from paper_1811_12019_amd import step as kstep        # noqa: E402
 from paper_1811_12019_amd import synth                # noqa: E402
 
 PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, TFLOP/s, GB/s
-# fp32 products computed as sums of bf16 x bf16 MFMAs over split operands: 6 MFMAs per fp32 product with both
-# operands split three ways (the sweep's rank-128 update), 3 with both split two ways (preconditioning)
+# fp32 products computed as sums of 16-bit MFMAs over split operands: 6 MFMAs per fp32 product with both operands
+# split into three bf16 pieces (the sweep's panel product), 3 with both split two ways (two bf16 pieces:
+# preconditioning; two fp16 pieces of scaled operands: the sweep's rank-128 updates); fp16 and bf16 MFMA peaks are equal
 PEAK["mfma_bf16x3"] = round(PEAK["mfma_bf16"] / 6, 1)
 PEAK["mfma_bf16x2"] = round(PEAK["mfma_bf16"] / 3, 1)
+PEAK["mfma_f16x2"] = PEAK["mfma_bf16x2"]
 
 
 def kernel_work(net: kstep.KfacNetworkStep):
@@ -49,7 +51,7 @@ def kernel_work(net: kstep.KfacNetworkStep):
     w = {
         # all steps of all matrices in one kernel; a matrix's last step (short product, dense mirrored output) is a
         # small part of it; it also inverts the next step's pivot block (fp32 matrix cores) beside the update
-        "inv_update_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s",
+        "inv_update_kernel": ("mfma", PEAK["mfma_f16x2"], "TFLOP/s",
                               sum(kstep.inverse_update_flops(d) + kstep.inverse_pivot_flops(d) - kstep.inverse_first_pivot_flops(d)
                                   for d in dims)),
         # latency-bound helpers of the sweep (one workgroup per matrix / per 128-row slab): first-block inverses of nb^3

@@ -8,6 +8,8 @@
 // v_mfma_f32_32x32x16_bf16 runs at 16 times the rate of v_mfma_f32_32x32x2_f32, so 3 (6) products per fp32
 // product still leave a factor 5.3 (2.7) over the fp32 matrix-core peak.
 //
+// (A variant with two fp16 pieces of scaled operands, three products, is at the end of this file.)
+//
 // One workgroup = 4 wavefronts in a 2 x 2 arrangement, each owning a 64 x 64 quadrant as 2 x 2 MFMA blocks.  K
 // advances 16 at a time through a double-buffered LDS stage: the next slab is fetched into registers while the
 // current one is multiplied, then split and stored to the other buffer; one barrier per slab.

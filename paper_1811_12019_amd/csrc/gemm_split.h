@@ -58,7 +58,8 @@ __device__ __forceinline__ void split4(const v4f& x, uint2 (&piece)[NS]) {
 // unguarded, every wavefront multiplies, and the stage loop is unrolled completely.  With no branches left the
 // compiler counts the loads in flight exactly instead of draining them at every join, which is what makes the
 // two-stage look-ahead effective.
-template <int NS, bool NEG_A = false, int NST = 0>
+// ROWS_ALIGN4 (with NST > 0): the panels' rows are only 4-byte aligned (odd leading dimension).
+template <int NS, bool NEG_A = false, int NST = 0, bool ROWS_ALIGN4 = false>
 __device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, int lda, int arows,
                                                   const gfloat* __restrict__ B, int ldb, int brows, int K,
                                                   unsigned char* __restrict__ lds, TileAcc& acc,
@@ -94,7 +95,10 @@ __device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, 
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int row = lr + 64 * p;
-            if constexpr (NST > 0) {
+            if constexpr (NST > 0 && ROWS_ALIGN4) {
+                xa[p] = *(const KFAC_AS1 v4f_a4*)(A + (size_t)row * lda + k0 + 4 * kq);
+                xb[p] = *(const KFAC_AS1 v4f_a4*)(B + (size_t)row * ldb + k0 + 4 * kq);
+            } else if constexpr (NST > 0) {
                 xa[p] = *(const KFAC_AS1 v4f*)(A + (size_t)row * lda + k0 + 4 * kq);
                 xb[p] = *(const KFAC_AS1 v4f*)(B + (size_t)row * ldb + k0 + 4 * kq);
             } else {

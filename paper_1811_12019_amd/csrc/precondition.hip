@@ -38,8 +38,14 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     int M, N, K;
     if (phase == 1) { A = as_global(it.Ainv); B = as_global(it.gradW); C = as_global((float*)it.ws); M = it.dA; N = it.dG; K = it.dA; }
     else            { A = as_global(it.Ginv); B = as_global((const float*)it.ws); C = as_global(it.out); M = it.dG; N = it.dA; K = it.dG; }
-    const int tn = (N + TM - 1) / TM;
-    const int ti = local / tn, tj = local - ti * tn;
+    // Workgroups go to the 8 XCDs round-robin, each with an L2 of its own.  Inside a block of 8 tile rows, the eight
+    // XCDs take one tile row each and walk along it: the tiles that share an A panel (128 rows of the inverse, the
+    // large operand when K is long) run on one L2, side by side, instead of on all eight (a third less traffic
+    // beyond L2).
+    const int tm = (M + TM - 1) / TM, tn = (N + TM - 1) / TM;
+    const int blk = local / (8 * tn), within = local - blk * 8 * tn;
+    const int rb = min(8, tm - 8 * blk);
+    const int ti = 8 * blk + within % rb, tj = within / rb;
     const int i0 = ti * TM, j0 = tj * TM;
     const int irows = min(TM, M - i0), jrows = min(TM, N - j0);
     TileAcc acc;
@@ -49,7 +55,17 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc.c[mb][nb][r] = 0.f;
-    tile_mma_nt_split<2>(A + (size_t)i0 * K, K, irows, B + (size_t)j0 * K, K, jrows, K, lds, acc);
+    // Interior tiles take the contraction 128 columns at a time through the unrolled, branch-free pipeline (two slabs
+    // of look-ahead with exact wait counts; the general loop has one slab of look-ahead and pays a memory round trip
+    // per slab, which a long contraction with few tiles cannot hide); the rest of K, and edge tiles, go the general way.
+    const gfloat* At = A + (size_t)i0 * K;
+    const gfloat* Bt = B + (size_t)j0 * K;
+    int kdone = 0;
+    if (irows == TM && jrows == TM) {
+        for (; kdone + 128 <= K; kdone += 128)
+            tile_mma_nt_split<2, false, 128 / SPLIT_KS, true>(At + kdone, K, TM, Bt + kdone, K, TM, 128, lds, acc);
+    }
+    if (kdone < K) tile_mma_nt_split<2>(At + kdone, K, irows, Bt + kdone, K, jrows, K - kdone, lds, acc);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)

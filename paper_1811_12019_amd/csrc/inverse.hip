@@ -886,24 +886,35 @@ __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* _
         const int h0 = half * 64;
         if (h0 >= c.irows) break;
         if (half == 1) __syncthreads();
+        // all eight loads go out before the first value is used (a use inside the guarded block would make the
+        // compiler wait for every load in turn)
+        v4f x[8];
         if (column) {
 #pragma unroll
             for (int p = 0; p < 8; ++p) {
-                const int rl = pr + 8 * p, row = h0 + rl;
-                v4f x = {0.f, 0.f, 0.f, 0.f};
-                if (row < c.irows) x = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.i0 + row) * NB + pc];
+                const int row = h0 + pr + 8 * p;
+                x[p] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (row < c.irows) x[p] = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.i0 + row) * NB + pc];
+            }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) lds[rl * sld + pc + i] = pc + i < c.nb ? x[i] : 0.f;
+            for (int p = 0; p < 8; ++p) {
+                const int rl = pr + 8 * p;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds[rl * sld + pc + i] = pc + i < c.nb ? x[p][i] : 0.f;
             }
         } else {
             const int ta = (t & 15) * 4, tc = t >> 4;     // 16 float4 along a (64 a's), 16 c's per pass
 #pragma unroll
             for (int p = 0; p < 8; ++p) {
                 const int cc = tc + 16 * p;
-                v4f x = {0.f, 0.f, 0.f, 0.f};
-                if (cc < c.jrows) x = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.j0 + cc) * NB + h0 + ta];
+                x[p] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (cc < c.jrows) x[p] = *(const KFAC_AS1 v4f*)&c.T[(size_t)(c.j0 + cc) * NB + h0 + ta];
+            }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) lds[(ta + i) * sld + cc] = h0 + ta + i < c.nb ? x[i] : 0.f;
+            for (int p = 0; p < 8; ++p) {
+                const int cc = tc + 16 * p;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds[(ta + i) * sld + cc] = h0 + ta + i < c.nb ? x[p][i] : 0.f;
             }
         }
         __syncthreads();

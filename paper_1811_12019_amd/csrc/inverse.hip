@@ -798,15 +798,26 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
     }
     // the products run on operands scaled by sa, sb (powers of two): the accumulators follow, exactly
     const float s0 = p0.sa * p0.sb;
+    // a tile with all its rows and columns, off the diagonal (nearly all of them): no guards, no branches
+    const bool whole = !c.diag && c.irows == NB && c.j0 + NB <= c.ldw;
+    if (whole) {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
+            for (int nbk = 0; nbk < 2; ++nbk)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
-                acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? oq[nbk][dr * o.rs] : 0.f;
-            }
+                for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = oq[nbk][(mb * 32 + (r >> 2) * 8 + (r & 3)) * o.rs];
+    } else {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                    acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? oq[nbk][dr * o.rs] : 0.f;
+                }
+    }
     TR(1);
     tile_mms_nt_split_h2<NB / SPLIT_KS>(p0.A, NB, p0.sa, p0.B, NB, p0.sb, lds, acc, s0);
     float back = 1.0f / s0;
@@ -821,15 +832,25 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
         for (int nbk = 0; nbk < 2; ++nbk) acc.c[mb][nbk] *= back;
     TR(3);
     if constexpr (STORE) {
+        if (whole) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int nbk = 0; nbk < 2; ++nbk)
+                for (int nbk = 0; nbk < 2; ++nbk)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
-                    if (colok[nbk] && dr < rows_left) wq[nbk][(size_t)dr * c.ldw] = acc.c[mb][nbk][r];
-                }
+                    for (int r = 0; r < 16; ++r)
+                        wq[nbk][(size_t)(mb * 32 + (r >> 2) * 8 + (r & 3)) * c.ldw] = acc.c[mb][nbk][r];
+        } else {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = mb * 32 + (r >> 2) * 8 + (r & 3);
+                        if (colok[nbk] && dr < rows_left) wq[nbk][(size_t)dr * c.ldw] = acc.c[mb][nbk][r];
+                    }
+        }
     }
     TR(5);
 }

@@ -133,14 +133,14 @@ __global__ __launch_bounds__(256) void inv_init_kernel(Batch b) {
     for (int r8 = 0; r8 < NB; r8 += 16) {
         float v[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = I * NB + r8 + 2 * i + rh;
-            v[i] = (row < d && col <= row) ? S[(size_t)row * d + col] + (row == col ? lam : 0.f) : 0.f;
+        for (int i = 0; i < 8; ++i) {                    // loads only: arithmetic on a guarded load would make the
+            const int row = I * NB + r8 + 2 * i + rh;    // compiler wait for each load in turn
+            v[i] = (row < d && col <= row) ? S[(size_t)row * d + col] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = I * NB + r8 + 2 * i + rh;
-            if (row < d && col < ws.ldw) ws.W[(size_t)row * ws.ldw + col] = v[i];
+            if (row < d && col < ws.ldw) ws.W[(size_t)row * ws.ldw + col] = v[i] + (row == col ? lam : 0.f);
         }
     }
 }
@@ -414,7 +414,7 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
                     const gfloat* src = it.S + (size_t)(k0 + row) * d + k0 + c4;
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (c4 + i <= row) x[i] = src[i] + (c4 + i == row ? it.damping : 0.f);
+                        if (c4 + i <= row) x[i] = src[i];            // (the damping is added at the LDS store below)
                 }
             }
             v[p] = x;
@@ -424,7 +424,7 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
             const int row = r0 + 8 * p;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (row < nb && c4 + i <= row) lds[tri_at(row, c4 + i)] = v[p][i];
+                if (row < nb && c4 + i <= row) lds[tri_at(row, c4 + i)] = v[p][i] + ((from_S && c4 + i == row) ? it.damping : 0.f);
         }
     }
     __syncthreads();

@@ -454,6 +454,20 @@ def test_damped_inverse_random_spd(dim):
     assert np.linalg.norm(M @ Minv - np.eye(dim)) / np.sqrt(dim) < 1e-3
 
 
+@pytest.mark.parametrize("scale", [1e-6, 1e-3, 1e3, 1e6])
+def test_damped_inverse_magnitudes(scale):
+    """Factors far from unit magnitude (the update's fp16 operand pieces rely on per-slab power-of-two scales): the
+    inverse of c (S + lambda I) is (1/c) times the inverse of S + lambda I, to the same relative accuracy."""
+    dim = 641
+    S = (synth.random_spd(dim, seed=11, eig_lo=1e-2, eig_hi=5.0) * scale).astype(np.float32)
+    lam = np.float32(0.05 * scale)
+    Minv, info = gpu_inverse(S, lam)
+    assert info == 0
+    ref = ko.damped_inverse(S, lam)
+    assert np.isfinite(Minv).all()
+    assert rel_fro(Minv, ref) < INV_TOL, rel_fro(Minv, ref)
+
+
 def test_damped_inverse_reads_lower_triangle_only():
     S = synth.random_spd(200, seed=4)
     junk = S.copy()

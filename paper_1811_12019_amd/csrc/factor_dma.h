@@ -221,8 +221,23 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
 
     // ---- epilogue (same as the register-transpose kernel) ----
     const int i0 = I * FT + wm * 64, j0 = J * FT + wn * 64;
+    // A tile wholly inside the matrix (nearly all of a large factor's) stores without per-element guards: 64 guards
+    // are 64 branches, and tiles of the widest layers have few rows to amortise them over.
+    const bool whole = (I + 1) * FT <= u.d && (J + 1) * FT <= u.d;
     if (nsplit > 1) {
         gfloat* dst = partial + ((size_t)split * ntiles + tile) * (FT * FT);
+        if (whole) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int row = wm * 64 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = wn * 64 + q * 32 + lm;
+                        dst[row * FT + col] = acc[p][q][r];
+                    }
+            return;
+        }
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
@@ -234,15 +249,27 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
                 }
         return;
     }
+    if (whole) {
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
+        for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
-                if (row < u.d && col < u.d) out[(size_t)row * u.d + col] = acc[p][q][r] * scale;
-            }
+                for (int r = 0; r < 16; ++r) {
+                    int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
+                    out[(size_t)row * u.d + col] = acc[p][q][r] * scale;
+                }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
+                    if (row < u.d && col < u.d) out[(size_t)row * u.d + col] = acc[p][q][r] * scale;
+                }
+    }
     if (diag) return;
     float* epi = (float*)smem + wave * (32 * FEPI_LD);
 #pragma unroll
@@ -254,11 +281,19 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
                 int row = (r >> 2) * 8 + h * 4 + (r & 3), col = q * 32 + lm;
                 epi[row * FEPI_LD + col] = acc[p][q][r] * scale;
             }
-        for (int c2 = 0; c2 < 64; c2 += 2) {
-            int c = c2 + h;
-            int col = j0 + c, row = i0 + p * 32 + lm;
-            float v = epi[lm * FEPI_LD + c];
-            if (col < u.d && row < u.d) out[(size_t)col * u.d + row] = v;
+        if (whole) {
+#pragma unroll 8
+            for (int c2 = 0; c2 < 64; c2 += 2) {
+                const int c = c2 + h;
+                out[(size_t)(j0 + c) * u.d + i0 + p * 32 + lm] = epi[lm * FEPI_LD + c];
+            }
+        } else {
+            for (int c2 = 0; c2 < 64; c2 += 2) {
+                int c = c2 + h;
+                int col = j0 + c, row = i0 + p * 32 + lm;
+                float v = epi[lm * FEPI_LD + c];
+                if (col < u.d && row < u.d) out[(size_t)col * u.d + row] = v;
+            }
         }
     }
 }

@@ -120,11 +120,13 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
             pix = ((n * u.H + y0) * u.W + x0) * u.C;
             yx = rvalid ? (((y0 + 0x4000) << 16) | (x0 + 0x4000)) : -1;      // -1: row outside the range
         }
+        // All four sources are worked out first, branch-free (the cross-lane exchanges go out back to back and are
+        // waited for once); then the DMA instructions, of which a diagonal tile issues only two.
+        gbyte* src[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (j >= ninstr) break;
             const int b = blk0 + j * blkstep;
-            const int k = 4 * b + dr;                                        // row inside the stage
+            const int k = (4 * b + dr) & (DK - 1);                           // row inside the stage (j >= ninstr: unused)
             // branch-free source selection: data element, the constant one-chunk (bias column), or zeros
             bool row_ok, tap_ok = true;
             size_t eoff;
@@ -142,9 +144,14 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
             }
             const bool is_data = row_ok && tap_ok && g.kind == 0;
             const bool is_one = row_ok && g.kind == 1;
-            gbyte* src = is_data ? xg + 2 * eoff : (is_one ? one_src : zero_src);
+            src[j] = is_data ? xg + 2 * eoff : (is_one ? one_src : zero_src);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j >= ninstr) break;
+            const int b = blk0 + j * blkstep;
             lds_byte* dst = lds0 + bufidx * DSTAGE + pan * DPANEL + b * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src[j],
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
         }
     };

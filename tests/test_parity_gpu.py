@@ -31,6 +31,13 @@ def rel_fro(got, want):
     return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300))
 
 
+def rel_max(got, want):
+    """Largest entry-wise error relative to the largest entry: a single misplaced entry cannot hide in it."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    return float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-300))
+
+
 def gpu_factor(op, shape, x_rounded, layout, dtype, order, scale=0.0):
     desc = kb.make_desc(shape, layout, dtype, order)
     xt = kb.to_device_tensor(x_rounded, layout, dtype, DEV)
@@ -55,6 +62,8 @@ def check_factor_pair(shape, layout, dtype, order, seed=0):
     assert np.isfinite(A).all() and np.isfinite(G).all()
     assert rel_fro(A, A_ref) < FACTOR_TOL, rel_fro(A, A_ref)
     assert rel_fro(G, G_ref) < FACTOR_TOL, rel_fro(G, G_ref)
+    assert rel_max(A, A_ref) < FACTOR_TOL, rel_max(A, A_ref)
+    assert rel_max(G, G_ref) < FACTOR_TOL, rel_max(G, G_ref)
     np.testing.assert_array_equal(A, A.T)
     np.testing.assert_array_equal(G, G.T)
     if shape.has_bias:
@@ -449,6 +458,7 @@ def test_damped_inverse_random_spd(dim):
     assert info == 0
     ref = ko.damped_inverse(S, lam)
     assert rel_fro(Minv, ref) < INV_TOL, rel_fro(Minv, ref)
+    assert rel_max(Minv, ref) < INV_TOL, rel_max(Minv, ref)
     np.testing.assert_array_equal(Minv, Minv.T)
     M = S.astype(np.float64) + lam * np.eye(dim)
     assert np.linalg.norm(M @ Minv - np.eye(dim)) / np.sqrt(dim) < 1e-3
@@ -505,8 +515,9 @@ def test_damped_inverse_config1_full_size():
     assert info == 0
     ref = ko.damped_inverse(S, lam)
     err = rel_fro(Minv, ref)
-    print(f"config1 inverse rel. Frobenius error {err:.3e}")
+    print(f"config1 inverse rel. Frobenius error {err:.3e}, largest entry-wise error / largest entry {rel_max(Minv, ref):.3e}")
     assert err < INV_TOL
+    assert rel_max(Minv, ref) < INV_TOL
     np.testing.assert_array_equal(Minv, Minv.T)
 
 
@@ -523,11 +534,36 @@ def test_damped_inverse_batched_mixed_sizes():
     for S, lam, M in zip(Ss, lams, Mt):
         got = M.cpu().numpy()
         assert rel_fro(got, ko.damped_inverse(S, np.float32(lam))) < INV_TOL
+        assert rel_max(got, ko.damped_inverse(S, np.float32(lam))) < INV_TOL
         np.testing.assert_array_equal(got, got.T)
     # same answer as one-at-a-time calls, bit for bit
     for S, lam, M in zip(Ss, lams, Mt):
         single, _ = gpu_inverse(S, lam)
         np.testing.assert_array_equal(single, M.cpu().numpy())
+
+
+def test_damped_inverse_batched_more_matrices_than_one_launch_group():
+    """70 small matrices of mixed size in one call: more than one launch's argument block describes, so the call
+    deals them into groups; every one against the oracle, and bit for bit against the single call."""
+    dims = [1 + (37 * i) % 300 for i in range(66)] + [385, 257, 129, 128]
+    Ss = [synth.random_spd(d, seed=100 + i, n_zero=d // 5) for i, d in enumerate(dims)]
+    lams = [0.02 + 0.001 * i for i in range(len(dims))]
+    St = [torch.from_numpy(s).to(DEV) for s in Ss]
+    Mt = [torch.full((d, d), float("nan"), dtype=torch.float32, device=DEV) for d in dims]
+    batch = kb.InverseBatch(St, Mt, lams, device=DEV)
+    assert batch.count == 70
+    kb.kfac_damped_inverse_batched(batch)
+    torch.cuda.synchronize()
+    assert batch.info.cpu().tolist() == [0] * len(dims)
+    for i, (S, lam, M) in enumerate(zip(Ss, lams, Mt)):
+        got = M.cpu().numpy()
+        ref = ko.damped_inverse(S, np.float32(lam))
+        assert rel_fro(got, ref) < INV_TOL, (i, dims[i])
+        assert rel_max(got, ref) < INV_TOL, (i, dims[i])
+        np.testing.assert_array_equal(got, got.T)
+        if i % 7 == 0:
+            single, _ = gpu_inverse(S, lam)
+            np.testing.assert_array_equal(single, got)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -552,6 +588,7 @@ def test_precondition(dG, dA):
     P = gpu_precondition(Ginv, Ainv, gradW)
     ref = ko.precondition(Ginv, gradW, Ainv)
     assert rel_fro(P, ref) < PRE_TOL, rel_fro(P, ref)
+    assert rel_max(P, ref) < PRE_TOL, rel_max(P, ref)
 
 
 def test_precondition_batched_matches_single_calls():

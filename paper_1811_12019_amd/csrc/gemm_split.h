@@ -297,4 +297,132 @@ __device__ __forceinline__ void tile_mms_nt_split_h2(const gfloat* __restrict__ 
     }
 }
 
+// ---- operands split ahead of time ----------------------------------------------------------------------------------
+// A panel (128-row slabs x 128 columns of the contraction index) that many tile products read is scaled and split
+// into its two fp16 pieces once, by the kernel that produces it, instead of by every product that consumes it: the
+// consumer then has no conversion work at all and moves the pieces from global memory straight into LDS
+// (global_load_lds_dwordx4: lane i's 16 bytes land at base + 16 i, no registers involved).  To make those copies
+// whole contiguous kilobytes, a piece plane is stored in the order the product wants it in LDS: slab by slab, and
+// inside a slab one 4 KB block per 16-wide slice of the contraction index, holding for every row its two 16-byte
+// halves (8 fp16 each) at byte offset split_plane_offset(row, half).  The halves swap places from one group of four rows
+// to the next and again from one group of eight to the next: a 16-byte operand read is served 16 lanes (consecutive rows)
+// at a time from 64 four-byte banks, and with this order any 16 consecutive rows' halves fall into 16 different
+// 16-byte bank groups (so do any 8 rows' in 8 of 32 banks); with rows simply 32 bytes apart, rows r and r + 8 collide.
+constexpr int PRE_BLOCK = 128 * SPLIT_KS * 2;          // bytes of one (slab, 16-wide slice) block of one piece plane
+constexpr int PRE_SLAB = (128 / SPLIT_KS) * PRE_BLOCK; // bytes of one 128 x 128 slab of one piece plane
+constexpr int PRE_STAGE = 4 * PRE_BLOCK;               // LDS per ring stage: A high, A low, B high, B low
+constexpr int PRE_NS = 3;                              // ring stages (two in flight)
+
+__host__ __device__ __forceinline__ int split_plane_offset(int row, int half) {
+    return row * 32 + ((half ^ ((row >> 2) & 1) ^ ((row >> 3) & 1)) * 16);
+}
+
+// Scaled fp16 pieces of four consecutive contraction-index values k4 .. k4 + 3 (k4 a multiple of 4) of one row of a
+// slab, written to the planes `hi` / `lo` (pointing at the slab).
+__device__ __forceinline__ void store_split4_h2(KFAC_AS1 unsigned char* hi, KFAC_AS1 unsigned char* lo, int row, int k4,
+                                                const v4f& x_scaled) {
+    uint2 piece[2];
+    split4_h2(x_scaled, piece);
+    const int off = (k4 >> 4) * PRE_BLOCK + split_plane_offset(row, (k4 >> 3) & 1) + (k4 & 7) * 2;
+    typedef unsigned v2u_t __attribute__((ext_vector_type(2)));
+    *(KFAC_AS1 v2u_t*)(hi + off) = v2u_t{piece[0].x, piece[0].y};
+    *(KFAC_AS1 v2u_t*)(lo + off) = v2u_t{piece[1].x, piece[1].y};
+}
+
+// The rank-128 products of a tile: product q reads the piece planes a_hi + q * stride (high pieces of the A slab), that
+// plus `plane` (low pieces), and likewise b_hi; scale[q] = sa * sb is what the product of the stored pieces is scaled by.
+template <int MAXN>
+struct SplitRun {
+    const KFAC_AS1 unsigned char* a_hi;
+    const KFAC_AS1 unsigned char* b_hi;
+    size_t plane;                                      // bytes from a high plane to its low plane
+    size_t stride;                                     // bytes from one product's planes to the next one's
+    float scale[MAXN];
+    int n;                                             // 1 .. MAXN products
+};
+
+// acc[128 x 128] (+)= sum over the products q of A_q B_q^T, A_q / B_q complete 128 x 128 slabs given as piece planes
+// (high x high + high x low + low x high on the fp16 matrix cores).  The products may be scaled differently: acc is
+// brought to product q's scale before it is added to (acc holds the caller's values, at scale 1, on entry), and the
+// returned factor brings it back to scale 1 (the caller multiplies).  lds: PRE_NS * PRE_STAGE bytes, 1 KB aligned.
+// All 256 threads must call; ends with the ring drained and a barrier.
+template <int MAXN>
+__device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsigned char* __restrict__ lds, TileAcc& acc) {
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    constexpr int NSL = 128 / SPLIT_KS;                // slices per product
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    lds_byte* l0 = (lds_byte*)lds;
+    unsigned a_addr[2], b_addr[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        a_addr[q] = (unsigned)split_plane_offset(wm * 64 + q * 32 + lm, h);
+        b_addr[q] = (unsigned)(2 * PRE_BLOCK + split_plane_offset(wn * 64 + q * 32 + lm, h));
+    }
+    const int nst = p.n * NSL;
+    const unsigned lane_off = (unsigned)(wave * 1024 + lane * 16);   // this lane's 16 bytes inside every block
+    auto issue = [&](int s, int buf) {
+        const int sc = s < nst ? s : nst - 1;          // past the end: re-read the last slice (never consumed)
+        const int q = sc / NSL, ks = sc - q * NSL;
+        const KFAC_AS1 unsigned char* pa = p.a_hi + q * p.stride;
+        const KFAC_AS1 unsigned char* pb = p.b_hi + q * p.stride;
+        const KFAC_AS1 unsigned char* src[4] = {pa, pa + p.plane, pb, pb + p.plane};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ks * PRE_BLOCK + lane_off),
+                                             (__attribute__((address_space(3))) void*)(l0 + buf * PRE_STAGE + j * PRE_BLOCK + wave * 1024),
+                                             16, 0, 0);
+    };
+    float back = 1.0f;
+    issue(0, 0);
+    issue(1, 1);
+    for (int it = 0; it < nst; it += PRE_NS) {
+#pragma unroll
+        for (int bi = 0; bi < PRE_NS; ++bi) {
+            const int s = it + bi;
+            if (s >= nst) break;                                            // uniform
+            asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");   // slice s landed (everybody's part)
+            issue(s + 2, (bi + 2) % PRE_NS);                                 // refill the slot slice s - 1 vacated
+            if (s % NSL == 0) {                                              // uniform: a new product begins
+                float sq = p.scale[0];
+#pragma unroll
+                for (int q = 1; q < MAXN; ++q) sq = s / NSL == q ? p.scale[q] : sq;
+                const float f = sq * back;
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) acc.c[mb][nb] *= f;
+                back = 1.0f / sq;
+            }
+            v4f a[2][2], b[2][2];                                            // (16 bytes = 8 fp16 each)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int pc = 0; pc < 2; ++pc) {
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[q][pc]) : "v"(a_addr[q]), "n"(bi * PRE_STAGE + pc * PRE_BLOCK));
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[q][pc]) : "v"(b_addr[q]), "n"(bi * PRE_STAGE + pc * PRE_BLOCK));
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]),
+                           "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]));
+            // smallest terms first
+#pragma unroll
+            for (int term = 0; term < 3; ++term)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                    {
+                        v8h av, bv;
+                        __builtin_memcpy(&av, &a[mb][term == 0 ? 1 : 0], 16);
+                        __builtin_memcpy(&bv, &b[nb][term == 1 ? 1 : 0], 16);
+                        acc.c[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc.c[mb][nb], 0, 0, 0);
+                    }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");            // ring idle: the LDS may be reused
+    return back;
+}
+
 }  // namespace kfac

@@ -33,18 +33,9 @@ namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
 constexpr int MAXB = 64;         // matrices per launch group (bounded by the 4 KB of kernel arguments)
-#ifndef UPD_WAVES
-#define UPD_WAVES 3
-#endif
+constexpr int UPD_WAVES = 3;     // wavefronts per SIMD the update kernel is compiled for (register budget)
 constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
 constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
-
-#ifdef KFAC_TILE_TRACE
-__device__ unsigned long long g_trace[4096 * 16];
-#define TR(slot) do { if (!LAST && threadIdx.x == 0 && blockIdx.x < 4096) { if (g_trace[blockIdx.x * 16 + (slot)] == 0) g_trace[blockIdx.x * 16 + (slot)] = wall_clock64(); } } while (0)
-#else
-#define TR(slot) do { } while (0)
-#endif
 
 // Everything a launch needs to know about its matrices travels in the kernel arguments (scalar loads, no dependent
 // memory round trip at the start of every workgroup).
@@ -52,6 +43,7 @@ struct Batch {
     int count;                        // matrices in this launch
     int prefix[MAXB + 1];             // workgroup prefix sums over them
     int dim[MAXB];
+    int step[MAXB];                   // the elimination step this launch takes for the matrix, or -1: none
     float damping[MAXB];
     const float* S[MAXB];
     float* Minv[MAXB];
@@ -92,35 +84,166 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
 
 static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }
 static inline __host__ __device__ int ldw_of(int dim) { return (dim + 31) / 32 * 32; }
-// Steps are taken in pairs (k even, k + 1) while neither is the matrix's last: the update launch of step k then
-// touches only the tiles that step k + 1's pivot and panel need (block row / column k + 1) and the pivot block after
-// next, and the launch of step k + 1 applies both steps' rank-128 updates to all other tiles in one pass over the
-// matrix.
-static inline __host__ __device__ bool pair_mode(int dim, int step) { return nblk_of(dim) > (step & ~1) + 2; }
-static inline __host__ __device__ int update_tiles(int dim, int step) {
+// Steps are taken in groups of up to GM consecutive blocks, none of them the matrix's last.  Inside a group only the
+// tiles that the group's remaining pivots and panels need are kept up to date step by step (block rows / columns of
+// the blocks still to come, all of them short lists: "narrow" launches); every other tile receives the group's
+// rank-128 updates together, in one pass over the matrix, in the launch of the group's last step ("wide"), which
+// cuts the traffic of the working copy by the group size.  The arithmetic per tile is the same sequence of fp32
+// operations as step-by-step updating.
+constexpr int GM = 4;
+struct Group {
+    int g0;      // first step of the group that `step` belongs to
+    int m;       // its size (1 .. GM); 0: `step` is the matrix's last step, which is never part of a group
+    int j;       // step - g0
+};
+static inline __host__ __device__ Group group_of(int dim, int step) {
     const int n = nblk_of(dim);
-    return (pair_mode(dim, step) && !(step & 1)) ? n + 1 : n * (n + 1) / 2;
+    Group g;
+    g.g0 = step / GM * GM;
+    g.j = step - g.g0;
+    g.m = min(GM, n - 1 - g.g0);
+    if (g.m < 0 || g.j >= g.m) g.m = 0;
+    return g;
+}
+// Tiles of the update launch of `step`, per matrix: "chain" tiles, which the following steps need at once, and "lag"
+// tiles.
+//   * Narrow launch (not the group's last step): chain = the tiles with an index among the blocks c still to come in
+//     the group (block row c: tiles (c, 0..c); block column c below the group: tiles (E.., c), E the first block after
+//     the group) and the diagonal tile (E, E), the first pivot block after the group; each sees this step only.
+//   * The group's last step: every other tile now owes the group's steps.  If a group of two or more steps follows,
+//     only the tiles that group needs at once are chain tiles (the same shape of list, for the next group's blocks;
+//     "urgent"); the rest of the matrix is dealt, as lag tiles, to that group's narrow launches, where it runs beside
+//     the pivot workgroups that set those launches' duration instead of prolonging this one.  Otherwise all tiles of
+//     the triangle are chain tiles (and in the matrix's last step, which writes the output).
+// The panels of two consecutive groups coexist in the NBUF buffers, so lag tiles read the previous group's.
+struct Plan {
+    Group g;
+    int kind;            // 0 narrow, 1 urgent, 2 whole triangle (group's last step), 3 whole triangle (matrix's last step)
+    int c_begin, c_end;  // kinds 0, 1: the list is built for blocks c_begin .. c_end - 1 (plus the diagonal tile c_end)
+    int chain;           // number of chain tiles
+    int lag;             // number of lag tiles in this launch
+    int lag_off;         // index of the first one in the lag list
+};
+constexpr int PLAN_NARROW = 0, PLAN_URGENT = 1, PLAN_WHOLE = 2, PLAN_LAST = 3;
+
+static inline __host__ __device__ int list_tiles(int n, int c_begin, int c_end) {
+    int t = 1;
+    for (int c = c_begin; c < c_end; ++c) t += c + 1 + n - c_end;
+    return t;
+}
+static inline __host__ __device__ Plan plan_of(int dim, int step) {
+    const int n = nblk_of(dim);
+    Plan p;
+    p.g = group_of(dim, step);
+    p.lag = p.lag_off = 0;
+    p.c_begin = p.c_end = 0;
+    if (p.g.m == 0) { p.kind = PLAN_LAST; p.chain = n * (n + 1) / 2; return p; }
+    const int E = p.g.g0 + p.g.m;
+    if (p.g.j < p.g.m - 1) {
+        p.kind = PLAN_NARROW;
+        p.c_begin = step + 1; p.c_end = E;
+        p.chain = list_tiles(n, p.c_begin, p.c_end);
+        if (p.g.g0 > 0) {                                   // the previous group left its update of the bulk to this one
+            const int nc = n - p.g.m;                       // (the tiles with no index inside this group)
+            const int total = nc * (nc + 1) / 2, per = (total + p.g.m - 2) / (p.g.m - 1);
+            p.lag_off = p.g.j * per;
+            p.lag = max(0, min(per, total - p.lag_off));
+        }
+        return p;
+    }
+    const Group next = group_of(dim, E);
+    if (next.m >= 2) {
+        p.kind = PLAN_URGENT;
+        p.c_begin = E; p.c_end = E + next.m;
+        p.chain = list_tiles(n, p.c_begin, p.c_end);
+    } else {
+        p.kind = PLAN_WHOLE;
+        p.chain = n * (n + 1) / 2;
+    }
+    return p;
+}
+static inline __host__ __device__ int update_tiles(int dim, int step) {
+    const Plan p = plan_of(dim, step);
+    return p.chain + p.lag;
+}
+// tile index of a narrow / urgent list -> (I, J)
+__device__ __forceinline__ void list_decode(int n, int c_begin, int c_end, int t, int& I, int& J) {
+    I = J = c_end;
+    for (int c = c_begin; c < c_end; ++c) {
+        const int cnt = c + 1 + n - c_end;
+        if (t < cnt) {
+            if (t <= c) { I = c; J = t; }
+            else { I = c_end + (t - c - 1); J = c; }
+            return;
+        }
+        t -= cnt;
+    }
+}
+// Index in the list of all lower tiles of an n x n tile triangle -> (I, J), in an order that keeps tiles sharing rows
+// and columns together: the triangle is cut into 8 x 8 super-blocks (row-major over the super-blocks, row-major inside
+// one).  A contiguous range of the list, which is what one XCD (one L2) gets, then reads about as many different T slabs
+// as U slabs, instead of a few T slabs and every U slab as in row-major order over the whole triangle.
+constexpr int SB = 8;
+__device__ __forceinline__ void tri_decode_blocked(int n, int t, int& I, int& J) {
+    int r0 = 0;
+    for (;;) {                                           // super-row with rows r0 .. r0 + h - 1
+        const int h = min(SB, n - r0);
+        const int cnt = h * r0 + h * (h + 1) / 2;        // full super-blocks to the left, then the triangular one
+        if (t < cnt || r0 + SB >= n) break;
+        t -= cnt;
+        r0 += SB;
+    }
+    const int h = min(SB, n - r0);
+    if (t < h * r0) {
+        const int sj = t / (h * SB), in = t - sj * (h * SB);
+        I = r0 + in / SB;
+        J = sj * SB + in % SB;
+    } else {
+        tri_decode(t - h * r0, I, J);
+        I += r0;
+        J += r0;
+    }
+}
+// index in the lag list of a group [E, E + m) -> (I, J): the lower triangle over the blocks outside the group
+__device__ __forceinline__ void lag_decode(int n, int E, int m, int t, int& I, int& J) {
+    tri_decode_blocked(n - m, t, I, J);
+    if (I >= E) I += m;
+    if (J >= E) J += m;
 }
 
+// Panels of one step, kept in buffer (step % NBUF): the fp32 copy U of block column k as it was before the step (all
+// rows, assembled from both triangles), the fp32 product T = U P, and the scaled fp16 pieces of both (the negated T and
+// U, each as a plane of high and a plane of low pieces in the layout of gemm_split.h), which the tile updates multiply.
+constexpr int NBUF = 2 * GM;
 struct WsView {
     gfloat* W;      // dim x ldw : working copy, lower triangle maintained
     int ldw;
-    gfloat* U[2];   // d_pad x NB : copy of block column k before step k (all rows, assembled from both triangles)
-    gfloat* T[2];   // d_pad x NB : U . P                                        ([k & 1]: two steps' panels coexist)
+    gfloat* buf0;   // NBUF panel buffers, `stride` floats each: U | T | -T high | -T low | U high | U low
+    size_t stride;
+    size_t plane;   // bytes of one piece plane (d_pad x NB fp16)
     gfloat* P;      // NB x NB    : inverse of the pivot block
-    gfloat* SC;     // 4 x nblk   : power-of-two scales of the 128-row slabs of T[0], U[0], T[1], U[1] (gemm_split.h)
+    gfloat* SC;     // 2 NBUF x nblk: power-of-two scales of the 128-row slabs of T and U of every buffer (gemm_split.h)
+    int nblk;
+    __device__ __forceinline__ gfloat* U(int q) const { return buf0 + q * stride; }
+    __device__ __forceinline__ gfloat* T(int q) const { return buf0 + q * stride + plane / 2; }
+    __device__ __forceinline__ KFAC_AS1 unsigned char* TH(int q) const { return (KFAC_AS1 unsigned char*)(buf0 + q * stride + plane); }
+    __device__ __forceinline__ KFAC_AS1 unsigned char* UH(int q) const { return TH(q) + 2 * plane; }
+    __device__ __forceinline__ gfloat& scaleT(int q, int slab) const { return SC[(q * 2 + 0) * nblk + slab]; }
+    __device__ __forceinline__ gfloat& scaleU(int q, int slab) const { return SC[(q * 2 + 1) * nblk + slab]; }
 };
+
+static inline __host__ __device__ size_t panel_buffer_floats(int dim) { return (size_t)nblk_of(dim) * NB * NB * 4; }
 
 __device__ inline WsView ws_view(gfloat* ws, int dim) {
     const size_t d_pad = (size_t)nblk_of(dim) * NB;
     WsView v;
     v.ldw = ldw_of(dim);
+    v.nblk = nblk_of(dim);
     v.W = ws;
-    v.U[0] = v.W + d_pad * v.ldw;
-    v.T[0] = v.U[0] + d_pad * NB;
-    v.U[1] = v.T[0] + d_pad * NB;
-    v.T[1] = v.U[1] + d_pad * NB;
-    v.P = v.T[1] + d_pad * NB;
+    v.buf0 = v.W + d_pad * v.ldw;
+    v.stride = panel_buffer_floats(dim);                 // 2 fp32 panels + 4 fp16 planes = 4 d_pad NB floats
+    v.plane = d_pad * NB * 2;
+    v.P = v.buf0 + NBUF * v.stride;
     v.SC = v.P + (size_t)NB * NB;
     return v;
 }
@@ -454,7 +577,8 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
 // slabs above the pivot), all 64 KB in flight at once, and the product then runs on the bf16 matrix cores with both
 // operands split three ways, reading the copy.  Ragged pivot block: fp32 matrix cores, operands guarded.
 constexpr int PANEL_TLD = NB + 1;          // LDS row stride of the transpose stage
-constexpr int PANEL_LDS_FLOATS = NB * PANEL_TLD;
+constexpr int PANEL_RLD = NB + 4;          // LDS row stride when the stage is read back four columns at a time
+constexpr int PANEL_LDS_FLOATS = NB * PANEL_RLD;
 static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
 
 // largest magnitude over the workgroup (every thread gets it); red: 4 floats of LDS
@@ -468,21 +592,23 @@ __device__ __forceinline__ float block_absmax(float x, float* __restrict__ red) 
     return x;
 }
 
-__global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
+__global__ __launch_bounds__(256) void inv_panel_kernel(Batch b) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
     __shared__ float red[4];
     int m, slab;
     locate(b, blockIdx.x, m, slab);
     const Item it = get_item(b, m);
     const int d = it.dim;
+    const int step = b.step[m];
     const int k0 = step * NB;
     const int nb = min(NB, d - k0);
     if (slab == step) return;                 // the pivot block's own rows are not needed
     const int r0 = slab * NB;
     const int rows = min(NB, d - r0);
     const WsView ws = ws_view(it.ws, d);
-    gfloat* __restrict__ Uc = ws.U[step & 1] + (size_t)r0 * NB;
-    gfloat* __restrict__ Tc = ws.T[step & 1] + (size_t)r0 * NB;
+    const int q = step % NBUF;
+    gfloat* __restrict__ Uc = ws.U(q) + (size_t)r0 * NB;
+    gfloat* __restrict__ Tc = ws.T(q) + (size_t)r0 * NB;
     const int t = threadIdx.x;
     TileAcc acc;
     if (nb == NB) {
@@ -520,7 +646,20 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) um = fmaxf(um, fabsf(v[p][i]));
         um = block_absmax(um, red);
-        if (t == 0) ws.SC[((step & 1) * 2 + 1) * nblk_of(d) + slab] = panel_scale(um);
+        const float su = panel_scale(um);
+        if (t == 0) ws.scaleU(q, slab) = su;
+        {   // the slab's scaled fp16 pieces (thread: columns c4 .. c4 + 3 of rows rr + 8 p, as in the copy above)
+            KFAC_AS1 unsigned char* uh = ws.UH(q) + (size_t)slab * PRE_SLAB;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                v4f x = v[p];
+                if (slab < step) {
+                    const float* src = &lds[(rr + 8 * p) * PANEL_TLD + c4];
+                    x = v4f{src[0], src[1], src[2], src[3]};
+                }
+                store_split4_h2(uh, uh + ws.plane, rr + 8 * p, c4, x * su);
+            }
+        }
         __threadfence_block();
         __syncthreads();                       // the copy is visible to the whole workgroup; the LDS stage is free
 #pragma unroll
@@ -536,6 +675,37 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
         tile_mma_nt<true>(ws.W + (size_t)k0 * ws.ldw + r0, ws.ldw, rows, ws.P, NB, nb, nb, lds, acc, Uc, NB);
     }
     const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    if (nb == NB) {
+        // T leaves through LDS, row-wise: the fp32 panel in 16-byte stores and its scaled, negated fp16 pieces
+        float tm = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tm = fmaxf(tm, fabsf(acc.c[mb][nbk][r]));
+        tm = block_absmax(tm, red);                       // (its barriers also separate the product's LDS use from this one)
+        const float st = panel_scale(tm);
+        if (t == 0) ws.scaleT(q, slab) = st;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    lds[acc_row(wm, mb, r, lane) * PANEL_RLD + acc_col(wn, nbk, lane)] = acc.c[mb][nbk][r];
+        __syncthreads();
+        const int c4 = (t & 31) * 4, rr = t >> 5;
+        KFAC_AS1 unsigned char* th = ws.TH(q) + (size_t)slab * PRE_SLAB;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = rr + 8 * p;
+            const v4f x = *(const v4f*)&lds[row * PANEL_RLD + c4];
+            if (row < rows) *(KFAC_AS1 v4f*)&Tc[(size_t)row * NB + c4] = x;
+            store_split4_h2(th, th + ws.plane, row, c4, x * -st);
+        }
+        return;
+    }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -545,17 +715,6 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b, int step) {
                 int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
                 if (row < rows) Tc[(size_t)row * NB + col] = col < nb ? acc.c[mb][nbk][r] : 0.f;
             }
-    if (nb == NB) {
-        float tm = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tm = fmaxf(tm, fabsf(acc.c[mb][nbk][r]));
-        tm = block_absmax(tm, red);
-        if (t == 0) ws.SC[((step & 1) * 2 + 0) * nblk_of(d) + slab] = panel_scale(tm);
-    }
     // the update streams whole 16-float slabs of T and U: keep the columns beyond a ragged block at zero
     if (nb < NB) {
         for (int e = t; e < rows * NB; e += 256) {
@@ -639,6 +798,7 @@ constexpr int UNS = 3;                    // ring stages
 constexpr int UPANEL = 8 * 1024;          // bytes per operand panel per stage
 constexpr int USTAGE = 2 * UPANEL;
 static_assert(UNS * USTAGE <= GEMM_LDS_FLOATS * 4 + 12288, "ring must fit the kernel's LDS");
+static_assert(UNS * USTAGE >= PRE_NS * PRE_STAGE, "the tile products' ring shares the kernel's LDS");
 
 #define KFAC_LDS_READ128(dst, addr, off) \
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
@@ -700,8 +860,6 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
         for (int nbk = 0; nbk < 2; ++nbk)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc.c[mb][nbk][r] = 0.f;
-
-    TR(1);
     issue(0, 0);
     issue(1, 1);
     for (int it = 0; it < nst; it += UNS) {
@@ -748,7 +906,6 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
                 oldv[p] = o;
             }
         }
-        TR(3 + 3 * half);
         if (wm == half) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -761,9 +918,7 @@ __device__ __forceinline__ void upd_regular(const UpdCtx& c, const gfloat* __res
                     }
         }
         __syncthreads();
-        TR(4 + 3 * half);
         upd_flush<LAST, true>(c, lds, h0, oldv);
-        TR(5 + 3 * half);
     }
 }
 
@@ -773,25 +928,35 @@ struct OldSrc {
     int rs, cs;
 };
 
-// Regular tile of a step that is not the matrix's last one: new = old - A0 B0^T (- A1 B1^T) goes back into the working
-// copy.  Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot
+// Regular tile of a step that is not the matrix's last one: new = old - A0 B0^T - A1 B1^T - ... (one product per pending
+// step, in step order) goes back into the working copy.  Only a matrix's last block can be ragged and the step that eliminates it is its last, so here the pivot
 // blocks are full (K = 128 per product).  The products run on the fp16 matrix cores with both operands scaled per
 // slab and split two ways (gemm_split.h): the accumulators start as the tile's old values (fetched straight into MFMA register layout:
 // register r of a 32 x 32 block is 32 consecutive floats of one row per half-wave), the negated products are added,
 // and the result is stored from the registers: nothing is staged in LDS.
-// p1.A == nullptr: one product.  STORE = false: the new values stay in acc (valid where the tile has rows and columns;
+// STORE = false: the new values stay in acc (valid where the tile has rows and columns;
 // the quadrant above the diagonal of a diagonal tile is not computed) and nothing is written.
-// One rank-128 product of a regular tile: T rows (with their slab's scale) and U rows (with theirs).
-struct PanelPair {
-    const gfloat* A;
-    const gfloat* B;
-    float sa, sb;
-};
+typedef SplitRun<GM> PanelRun;
+
+// The products of tile (I, J) with the panels of buffers first .. first + n - 1 (consecutive steps of one group).
+__device__ __forceinline__ PanelRun panel_run(const WsView& ws, int first, int n, int I, int J) {
+    PanelRun r;
+    r.a_hi = ws.TH(first) + (size_t)I * PRE_SLAB;
+    r.b_hi = ws.UH(first) + (size_t)J * PRE_SLAB;
+    r.plane = ws.plane;
+    r.stride = ws.stride * sizeof(float);
+    r.n = n;
+#pragma unroll
+    for (int q = 0; q < GM; ++q) {
+        const int b = min(first + q, NBUF - 1);
+        r.scale[q] = ws.scaleT(b, I) * ws.scaleU(b, J);
+    }
+    return r;
+}
 
 template <bool STORE = true>
-__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const OldSrc& o, const PanelPair& p0,
-                                                      const PanelPair& p1, unsigned char* __restrict__ lds, TileAcc& acc) {
-    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
+__device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const OldSrc& o, const PanelRun& pl,
+                                                      unsigned char* __restrict__ lds, TileAcc& acc) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, h = lane >> 5;
     const bool dead = c.diag && wm == 0 && wn == 1;      // strictly above the diagonal, never used
@@ -807,7 +972,6 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
         oq[nbk] = o.base + (wm * 64 + 4 * h) * o.rs + (wn * 64 + nbk * 32 + lm) * o.cs;
     }
     // the products run on operands scaled by sa, sb (powers of two): the accumulators follow, exactly
-    const float s0 = p0.sa * p0.sb;
     // a tile with all its rows and columns, off the diagonal (nearly all of them): no guards, no branches
     const bool whole = !c.diag && c.irows == NB && c.j0 + NB <= c.ldw;
     if (whole) {
@@ -828,19 +992,11 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
                     acc.c[mb][nbk][r] = (colok[nbk] && dr < rows_left) ? oq[nbk][dr * o.rs] : 0.f;
                 }
     }
-    TR(1);
-    tile_mms_nt_split_h2<NB / SPLIT_KS>(p0.A, NB, p0.sa, p0.B, NB, p0.sb, lds, acc, s0);
-    float back = 1.0f / s0;
-    if (p1.A) {                                          // uniform
-        const float s1 = p1.sa * p1.sb;
-        tile_mms_nt_split_h2<NB / SPLIT_KS>(p1.A, NB, p1.sa, p1.B, NB, p1.sb, lds, acc, s1 * back);
-        back = 1.0f / s1;
-    }
+    const float back = tile_mma_presplit(pl, lds, acc);  // (what brings acc back to the scale of the tile)
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int nbk = 0; nbk < 2; ++nbk) acc.c[mb][nbk] *= back;
-    TR(3);
     if constexpr (STORE) {
         if (whole) {
 #pragma unroll
@@ -862,7 +1018,6 @@ __device__ __forceinline__ void upd_regular_mid_split(const UpdCtx& c, const Old
                     }
         }
     }
-    TR(5);
 }
 
 // Look-ahead: the diagonal tile that is the next step's pivot block is updated by a workgroup of its own, which
@@ -873,7 +1028,8 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     const WsView ws = ws_view(it.ws, d);
     const int k0 = kn * NB, nb = min(NB, d - k0);
     UpdCtx c;
-    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T[step & 1]; c.out = it.Minv;
+    const int cur = step % NBUF;                         // (the block is kept up to date through the step before)
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T(cur); c.out = it.Minv;
     c.d = d;
     c.i0 = c.j0 = k0;
     c.irows = c.jrows = nb;
@@ -881,12 +1037,8 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     c.diag = true;
     TileAcc acc;
     const OldSrc o = {ws.W + (size_t)k0 * ws.ldw + k0, ws.ldw, 1};
-    const size_t po = (size_t)k0 * NB;                   // the block's rows in the panels
-    const int cur = step & 1;                            // (in a pair's second step the block has seen the first already)
-    const int nblk = nblk_of(d);
-    const PanelPair p0 = {ws.T[cur] + po, ws.U[cur] + po, ws.SC[(cur * 2 + 0) * nblk + kn], ws.SC[(cur * 2 + 1) * nblk + kn]};
-    const PanelPair none = {nullptr, nullptr, 1.f, 1.f};
-    upd_regular_mid_split<false>(c, o, p0, none, (unsigned char*)lds, acc);
+    const PanelRun pl = panel_run(ws, cur, 1, kn, kn);
+    upd_regular_mid_split<false>(c, o, pl, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
@@ -953,12 +1105,50 @@ __device__ __forceinline__ void upd_panel(const UpdCtx& c, bool column, float* _
     }
 }
 
+// Tile (I, J) of a step that is not the matrix's last: brings it up to date through step kq = g.g0 + g.j of group g.
+// single: the tile has been kept up to date step by step (a narrow launch): it sees step kq only, and its old value
+// is in the working copy.  Otherwise it sees all of the group's steps up to kq that it has not seen yet: all of them
+// for a tile with no index inside the group.  A tile with an index inside the group was kept up to date until its
+// later such index c was eliminated (when it became part of panel c: T_I for a tile of block column c, T_J transposed
+// for a tile of block row c, neither written to the working copy then), and sees the steps after c; the diagonal tile
+// (c, c) is -P_c, which the pivot code did write.
+__device__ __forceinline__ void group_tile(const Item& it, const WsView& ws, int I, int J, const Group& g, bool single,
+                                           float* __restrict__ lds) {
+    const int kq = g.g0 + g.j;
+    const int gbuf = g.g0 % NBUF;                        // buffer of the group's first step
+    UpdCtx c;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T(gbuf + g.j); c.out = it.Minv;
+    c.d = it.dim;
+    c.i0 = I * NB; c.j0 = J * NB;
+    c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
+    c.nb = NB;                                           // (only a matrix's last block can be ragged)
+    c.diag = I == J;
+    if (J == kq || I == kq) {                            // block column / row kq becomes the panel
+        upd_panel<false>(c, J == kq, lds);
+        return;
+    }
+    OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
+    int first = g.j;                                     // steps first .. g.j of the group, in order
+    if (!single) {
+        const bool inI = I >= g.g0 && I < kq, inJ = J >= g.g0 && J < kq;
+        first = 0;
+        if (inI) {                                       // I is the later index (I >= J)
+            first = I - g.g0 + 1;
+            if (I != J) o = OldSrc{ws.T(gbuf + I - g.g0) + (size_t)c.j0 * NB, 1, NB};
+        } else if (inJ) {                                // I lies beyond the group
+            first = J - g.g0 + 1;
+            o = OldSrc{ws.T(gbuf + J - g.g0) + (size_t)c.i0 * NB, NB, 1};
+        }
+    }
+    TileAcc acc;
+    const PanelRun run = panel_run(ws, gbuf + first, g.j - first + 1, I, J);
+    upd_regular_mid_split(c, o, run, (unsigned char*)lds, acc);
+}
+
 // One launch per step for all matrices of the batch that still have a block `step`; a matrix whose last block this
 // is takes the output-writing paths (LAST), the others update their working copies.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b, int step) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b) {
     __shared__ __attribute__((aligned(1024))) float lds[UNS * USTAGE / 4];
-    [[maybe_unused]] constexpr bool LAST = false;        // (for the tracing macro)
-    TR(0);
     // Workgroups go to the 8 XCDs round-robin (id % 8) and each XCD has an L2 of its own.  XCD x therefore takes the
     // x-th contiguous eighth of the tile list (matrix by matrix, row-major over the lower triangle): tiles that
     // share a T panel (same block row) and mostly the same U panels run on the same L2 instead of all eight.
@@ -968,7 +1158,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     if ((int)blockIdx.x < npiv) {
         if ((int)blockIdx.x >= b.count) return;
         const Item it = get_item(b, blockIdx.x);
-        if (nblk_of(it.dim) > step + 1) upd_next_pivot(it, step, lds);
+        const int step = b.step[blockIdx.x];
+        if (step >= 0 && nblk_of(it.dim) > step + 1) upd_next_pivot(it, step, lds);
         return;
     }
     const unsigned bx = blockIdx.x - npiv;
@@ -980,55 +1171,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     locate(b, lin, m, tile);
     const Item it = get_item(b, m);
     const int nblk = nblk_of(it.dim);
-    const int kb = step;
-    const bool pm = pair_mode(it.dim, step);
-    const bool narrow = pm && !(step & 1), wide = pm && (step & 1);
-    int I, J;
-    if (narrow) {                               // block row / column kb + 1: (kb+1, 0..kb+1), (kb+2.., kb+1); (kb+2, kb+2)
-        if (tile <= kb + 1) { I = kb + 1; J = tile; }
-        else if (tile < nblk) { I = tile; J = kb + 1; }
-        else { I = J = kb + 2; }
-    } else {
-        tri_decode(tile, I, J);
-    }
-    if (I == J && (I == kb || I == kb + 1)) return;     // this step's pivot block and the next one's are written elsewhere
-    const bool last = nblk == step + 1;                 // uniform per workgroup
+    const int step = b.step[m];
+    const Plan pl = plan_of(it.dim, step);
     const WsView ws = ws_view(it.ws, it.dim);
-    const int cur = step & 1;
+    int I, J;
+    if (tile >= pl.chain) {
+        // lag tile: the whole update of the previous group (steps g0 - GM .. g0 - 1, all GM of them)
+        lag_decode(nblk, pl.g.g0, pl.g.m, pl.lag_off + tile - pl.chain, I, J);
+        const int E = pl.g.g0 + pl.g.m;
+        if (I == J && (I == pl.g.g0 - 1 || I == E)) return;   // -P of the group's last step; a chain tile of this group
+        Group pg;
+        pg.g0 = pl.g.g0 - GM; pg.m = GM; pg.j = GM - 1;
+        group_tile(it, ws, I, J, pg, false, lds);
+        return;
+    }
+    if (pl.kind == PLAN_NARROW || pl.kind == PLAN_URGENT) list_decode(nblk, pl.c_begin, pl.c_end, tile, I, J);
+    else tri_decode_blocked(nblk, tile, I, J);
+    if (I == J && (I == step || I == step + 1)) return;  // this step's pivot block and the next one's are written elsewhere
+    if (pl.kind != PLAN_LAST) {
+        group_tile(it, ws, I, J, pl.g, pl.kind == PLAN_NARROW, lds);
+        return;
+    }
+    const int cur = step % NBUF;
     UpdCtx c;
-    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T[cur]; c.out = it.Minv;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T(cur); c.out = it.Minv;
     c.d = it.dim;
     c.i0 = I * NB; c.j0 = J * NB;
     c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
     c.nb = min(NB, c.d - step * NB);
     c.diag = I == J;
-    if (J == kb || I == kb) {                           // block column / row kb becomes the panel
-        if (last) upd_panel<true>(c, J == kb, lds);
-        else upd_panel<false>(c, J == kb, lds);
-        return;
-    }
-    if (last) { upd_regular<true>(c, ws.U[cur], lds); return; }
-    TileAcc acc;
-    auto pair_of = [&](int buf) {
-        return PanelPair{ws.T[buf] + (size_t)c.i0 * NB, ws.U[buf] + (size_t)c.j0 * NB, ws.SC[(buf * 2 + 0) * nblk + I],
-                         ws.SC[(buf * 2 + 1) * nblk + J]};
-    };
-    // One step: new = old - T_I U_J^T.  Second step of a pair (steps k = kb - 1 and kb): tiles outside block rows /
-    // columns kb have not seen step k yet.
-    OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
-    PanelPair p0 = pair_of(cur), p1 = {nullptr, nullptr, 1.f, 1.f};
-    const int k = kb - 1;
-    if (wide && !(I == k && J == k)) {                  // (block (k, k) is -P_k, written by the pivot code)
-        if (J == k) {                                   // block column k: step k would have stored T_I (its panel)
-            o = OldSrc{ws.T[cur ^ 1] + (size_t)c.i0 * NB, NB, 1};
-        } else if (I == k) {                            // block row k: step k would have stored T_J transposed
-            o = OldSrc{ws.T[cur ^ 1] + (size_t)c.j0 * NB, 1, NB};
-        } else {                                        // both steps' updates in one pass
-            p1 = p0;
-            p0 = pair_of(cur ^ 1);
-        }
-    }
-    upd_regular_mid_split(c, o, p0, p1, (unsigned char*)lds, acc);
+    if (J == step || I == step) upd_panel<true>(c, J == step, lds);
+    else upd_regular<true>(c, ws.U(cur), lds);
 }
 
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
@@ -1066,17 +1239,29 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
     b.prefix[0] = 0;
     for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
     KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
-    for (int step = 0; step < max_steps; ++step) {
-        int active = 0;   // multi-block matrices that still have a block `step`
-        while (active < n_multi && nblk_of(h[active].dim) > step) ++active;
-        if (active == 0) break;
-        b.count = active;
-        if (step == 0) KFAC_LAUNCH(inv_pivot_kernel, dim3(active), dim3(256), stream, b, step, 0);   // later ones: by the update
-        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + nblk_of(h[i].dim);
-        KFAC_LAUNCH(inv_panel_kernel, dim3(b.prefix[active]), dim3(256), stream, b, step);
-        b.count = active;
-        for (int i = 0; i < active; ++i) b.prefix[i + 1] = b.prefix[i] + update_tiles(h[i].dim, step);
-        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(active) + xcd_grid(b.prefix[active])), dim3(256), stream, b, step);
+    // One panel and one update launch per step of the matrix with the most blocks.  A matrix with fewer blocks takes
+    // its steps at evenly spread launches rather than in the first ones: the tile updates of the whole batch are then
+    // spread over all launches, each of which lasts at least as long as a pivot workgroup anyway.
+    int done[MAXB] = {};                                // steps taken so far
+    KFAC_LAUNCH(inv_pivot_kernel, dim3(n_multi), dim3(256), stream, b, 0, 0);   // first blocks (later ones: by the update)
+    for (int l = 0; l < max_steps; ++l) {
+        int panel_wgs = 0, update_wgs = 0;
+        for (int i = 0; i < n_multi; ++i) {
+            // (a matrix's last two steps touch all of its tiles, the last one on a slow path: matrices with fewer blocks
+            // than the largest finish at different launches, none with the largest ones)
+            const int n = nblk_of(h[i].dim);
+            const int span = n == max_steps ? n : max(n, max_steps - 2 - 2 * (i % 6));
+            const bool run = l < span && (int)(((long long)(l + 1) * n) / span) > (int)(((long long)l * n) / span);
+            b.step[i] = run ? done[i] : -1;
+        }
+        for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + (b.step[i] >= 0 ? nblk_of(h[i].dim) : 0);
+        panel_wgs = b.prefix[n_multi];
+        KFAC_LAUNCH(inv_panel_kernel, dim3(panel_wgs), dim3(256), stream, b);
+        for (int i = 0; i < n_multi; ++i)
+            b.prefix[i + 1] = b.prefix[i] + (b.step[i] >= 0 ? update_tiles(h[i].dim, b.step[i]) : 0);
+        update_wgs = b.prefix[n_multi];
+        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(n_multi) + xcd_grid(update_wgs)), dim3(256), stream, b);
+        for (int i = 0; i < n_multi; ++i) done[i] += b.step[i] >= 0;
     }
     return KFAC_OK;
 }
@@ -1084,7 +1269,7 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
 static size_t ws_bytes_of(int dim) {
     if (nblk_of(dim) == 1) return 256;
     const size_t d_pad = (size_t)nblk_of(dim) * NB;
-    return align_up((d_pad * ldw_of(dim) + 4 * d_pad * NB + (size_t)NB * NB + 4 * (size_t)nblk_of(dim)) * sizeof(float), 256);
+    return align_up((d_pad * ldw_of(dim) + NBUF * panel_buffer_floats(dim) + (size_t)NB * NB + 2 * NBUF * (size_t)nblk_of(dim)) * sizeof(float), 256);
 }
 
 static bool item_ok(const kfac_inverse_item& it) {
@@ -1132,16 +1317,3 @@ extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, 
     }
     return KFAC_OK;
 }
-
-#ifdef KFAC_TILE_TRACE
-// Debug builds only: copies the tile-phase timestamps to the host and clears them.
-extern "C" int kfac_debug_trace_read(unsigned long long* host, size_t count) {
-    if (count > 4096 * 16) return KFAC_ERR_INVALID_ARG;
-    if (hipDeviceSynchronize() != hipSuccess) return KFAC_ERR_HIP;
-    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(kfac::g_trace), count * sizeof(unsigned long long)) != hipSuccess) return KFAC_ERR_HIP;
-    void* p = nullptr;
-    if (hipGetSymbolAddress(&p, HIP_SYMBOL(kfac::g_trace)) != hipSuccess) return KFAC_ERR_HIP;
-    if (hipMemset(p, 0, 4096 * 16 * sizeof(unsigned long long)) != hipSuccess) return KFAC_ERR_HIP;
-    return KFAC_OK;
-}
-#endif

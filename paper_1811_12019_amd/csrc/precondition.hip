@@ -24,7 +24,7 @@ struct PBatch {
 
 // phase 1: Yt[dA x dG] = Ainv . gradW^T      phase 2: out[dG x dA] = Ginv . Yt^T
 __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[split_lds_bytes<2>()];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[split_lds_bytes<3>()];
     int lo = 0, hi = b.count;
     const int wg = blockIdx.x;
     while (hi - lo > 1) {
@@ -63,9 +63,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     int kdone = 0;
     if (irows == TM && jrows == TM) {
         for (; kdone + 128 <= K; kdone += 128)
-            tile_mma_nt_split<2, false, 128 / SPLIT_KS, true>(At + kdone, K, TM, Bt + kdone, K, TM, 128, lds, acc);
+            tile_mma_nt_split<3, false, 128 / SPLIT_KS, true>(At + kdone, K, TM, Bt + kdone, K, TM, 128, lds, acc);
     }
-    if (kdone < K) tile_mma_nt_split<2>(At + kdone, K, irows, Bt + kdone, K, jrows, K - kdone, lds, acc);
+    if (kdone < K) tile_mma_nt_split<3>(At + kdone, K, irows, Bt + kdone, K, jrows, K - kdone, lds, acc);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)

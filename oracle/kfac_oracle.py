@@ -92,6 +92,41 @@ def factor_damping(gamma: float) -> float:
     return float(np.sqrt(gamma))
 
 
+def pi_correction(A, G) -> float:
+    """Trace-ratio factor pi of the factored Tikhonov damping of Martens & Grosse (2015), the technique Sec. 4.2 names for
+    the Kronecker-factored block: pi = sqrt((tr A / d_A) / (tr G / d_G)), the ratio of the factors' mean eigenvalues.
+    (The paper cites the technique without a formula; this is the cited paper's.)"""
+    A = np.asarray(A, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    mean_a = np.trace(A) / A.shape[0]
+    mean_g = np.trace(G) / G.shape[0]
+    return float(np.sqrt(mean_a / mean_g))
+
+
+def factor_damping_pi(A, G, gamma: float):
+    """Per-factor diagonal shifts (lambda_A, lambda_G) = (pi sqrt(gamma), sqrt(gamma) / pi): the block damping gamma
+    split between the factors in proportion to their scale, so that (A + lambda_A I) (x) (G + lambda_G I) differs from
+    A (x) G + gamma I by cross terms of equal average size.  pi = 1 gives factor_damping's even split."""
+    pi = pi_correction(A, G)
+    root = float(np.sqrt(gamma))
+    return pi * root, root / pi
+
+
+def warmup_damping_alpha(gamma0: float, gamma_target: float, t_warmup: float) -> float:
+    """alpha = 2 log10(gamma0 / gamma_target) / t_warmup (Sec. 4.2, warm-up damping)."""
+    return 2.0 * float(np.log10(gamma0 / gamma_target)) / float(t_warmup)
+
+
+def warmup_damping_next(gamma: float, gamma_target: float, alpha: float) -> float:
+    """gamma(t+1) = (1 - alpha) gamma(t) + alpha gamma_target (Sec. 4.2)."""
+    return (1.0 - alpha) * gamma + alpha * gamma_target
+
+
+def bn_damping(gamma: float, rho_bn: float) -> float:
+    """Damping of the Batch Normalization layers, rho_BN times the current gamma (Sec. 4.2)."""
+    return float(rho_bn) * float(gamma)
+
+
 def damped_inverse(S, damping: float) -> np.ndarray:
     """(S + damping * I)^-1 for symmetric S."""
     S = np.asarray(S, dtype=np.float64)

@@ -490,3 +490,47 @@ def test_bn_precondition_diag_and_full():
     # a diagonal Fisher matrix: both forms agree; by hand: diag (1, 3), grad (2, 2), damping 1 -> (1, 0.5)
     np.testing.assert_allclose(ko.bn_precondition_diag([1.0, 3.0], [2.0, 2.0], 1.0), [1.0, 0.5])
     np.testing.assert_allclose(ko.bn_precondition_full(np.diag([1.0, 3.0]), [2.0, 2.0], 1.0), [1.0, 0.5])
+
+
+# ---------------------------------------------------------------------------------------------------
+# damping: trace-ratio split between the factors, warm-up schedule (Sec. 4.2)
+# ---------------------------------------------------------------------------------------------------
+def test_pi_corrected_damping_split():
+    # by hand: mean eigenvalue of A = 4, of G = 1 -> pi = 2 -> (2 sqrt(gamma), sqrt(gamma) / 2)
+    A, G = np.diag([4.0, 4.0]), np.diag([1.0, 1.0, 1.0])
+    assert ko.pi_correction(A, G) == pytest.approx(2.0)
+    la, lg = ko.factor_damping_pi(A, G, 1e-2)
+    assert la == pytest.approx(0.2) and lg == pytest.approx(0.05)
+    # equal scales: the even split of factor_damping
+    la, lg = ko.factor_damping_pi(np.eye(5), np.eye(3), 1e-3)
+    assert la == pytest.approx(ko.factor_damping(1e-3)) and lg == pytest.approx(ko.factor_damping(1e-3))
+    # general factors: the two shifts multiply to gamma, and the two cross terms of
+    # (A + la I) (x) (G + lg I) - A (x) G - gamma I, namely lg (A (x) I) and la (I (x) G), have equal traces per dimension
+    rng = np.random.default_rng(21)
+    X, Y = rng.standard_normal((30, 7)), 0.1 * rng.standard_normal((30, 4))
+    A, G = X.T @ X / 30, Y.T @ Y / 30
+    la, lg = ko.factor_damping_pi(A, G, 3e-4)
+    assert la * lg == pytest.approx(3e-4, rel=1e-12)
+    full = np.kron(A + la * np.eye(7), G + lg * np.eye(4)) - np.kron(A, G) - 3e-4 * np.eye(28)
+    np.testing.assert_allclose(full, lg * np.kron(A, np.eye(4)) + la * np.kron(np.eye(7), G), atol=1e-15)
+    assert np.trace(lg * np.kron(A, np.eye(4))) == pytest.approx(np.trace(la * np.kron(np.eye(7), G)), rel=1e-12)
+    # scaling A by c^2 scales pi by c
+    assert ko.pi_correction(9.0 * A, G) == pytest.approx(3.0 * ko.pi_correction(A, G), rel=1e-12)
+
+
+def test_warmup_damping_schedule(paper_values):
+    g0, gt = paper_values["warmup_gamma0_bs4096"], paper_values["warmup_gamma_target_bs4096"]
+    tw = paper_values["warmup_steps_bs4096"]
+    alpha = ko.warmup_damping_alpha(g0, gt, tw)
+    assert alpha == pytest.approx(4.0 / 313.0, rel=1e-12)            # log10(100) = 2, by hand
+    assert ko.warmup_damping_alpha(2.0e-2, 2.0e-4, paper_values["warmup_steps_bs32768"]) == pytest.approx(4.0 / 59.0)
+    # one step by hand: 0.025 (1 - 4/313) + 0.00025 (4/313)
+    assert ko.warmup_damping_next(g0, gt, alpha) == pytest.approx(0.025 - 0.02475 * 4.0 / 313.0, rel=1e-12)
+    # closed form of the recurrence: gamma(t) - gamma_target = (1 - alpha)^t (gamma(0) - gamma_target)
+    g = g0
+    for t in range(1, 401):
+        g = ko.warmup_damping_next(g, gt, alpha)
+        assert g == pytest.approx(gt + (1.0 - alpha) ** t * (g0 - gt), rel=1e-10)
+        assert gt < g < g0                                           # decreasing towards the target, never below it
+    assert ko.warmup_damping_next(gt, gt, alpha) == pytest.approx(gt)    # the target is the fixed point
+    assert ko.bn_damping(2.5e-4, paper_values["warmup_rho_bn_bs4096"]) == pytest.approx(4.0e-3)

@@ -13,7 +13,9 @@
  *
  * Conventions common to every call
  *   - Every pointer is a DEVICE pointer unless its name ends in `_host`.  The caller owns every
- *     buffer; the library allocates nothing, frees nothing and keeps no state between calls.
+ *     buffer; the library allocates no device memory and frees none, and no result depends on an
+ *     earlier call.  The one piece of process-wide state is the measurement aid at the end of this
+ *     file (a flag and, while it is on, the list of recorded events); it is off by default.
  *     Scratch memory comes in through `ws` / `ws_bytes`; the *_workspace_bytes functions (pure
  *     host functions) say how much a call needs.  `ws` must be 256-byte aligned.
  *   - Matrices are dense, row-major, with leading dimension = number of columns, float32.
@@ -23,7 +25,8 @@
  *   - Return value: KFAC_OK or a negative kfac_status.  Argument errors are detected on the host
  *     before anything is launched.  Numerical failure of an inversion (matrix not positive
  *     definite) is reported through the device-side `info` word, LAPACK potrf style.
- *   - Thread safety: calls on different streams with disjoint buffers may run concurrently.
+ *   - Thread safety: calls from different host threads, on different streams, with disjoint buffers
+ *     may run concurrently (the measurement aid takes a lock of its own when it is on).
  */
 #ifndef KFAC_H_
 #define KFAC_H_

@@ -10,6 +10,7 @@
 // can split the R unfolded rows over several workgroups (deterministic two-pass reduction through
 // the caller's workspace, no float atomics).
 #include <cstdlib>
+#include <mutex>
 
 #include "common.h"
 #include "factor_mfma.h"
@@ -247,6 +248,8 @@ static __host__ __device__ bool dma_eligible(const Unfold& u) {
     if (u.dtype != KFAC_BF16 && u.dtype != KFAC_F16) return false;
     if (u.layout != KFAC_NHWC || (u.C & 7)) return false;
     if (u.order != KFAC_ORDER_KH_KW_C && !(u.kh == 1 && u.kw == 1)) return false;
+    // the kernel packs a row's patch origin (y0, x0), each offset by 16384, into one 32-bit word
+    if (u.H + u.pad >= 16384 || u.W + u.pad >= 16384 || u.pad >= 16384) return false;
     return u.R < (1 << 24);
 }
 
@@ -314,11 +317,8 @@ __device__ __forceinline__ int fbatch_locate(const FBatch& b, int wg, int& local
     return lo;
 }
 
-#ifndef FACTOR_WAVES
-#define FACTOR_WAVES 2
-#endif
 template <bool PLAIN, bool F16>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FACTOR_WAVES, 8))) void factor_dma_kernel(FBatch b) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) void factor_dma_kernel(FBatch b) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     int local;
     const int m = fbatch_locate(b, blockIdx.x, local);
@@ -370,12 +370,11 @@ static int check_item(const kfac_factor_item& it, Unfold* u) {
 
 template <bool PLAIN, bool F16>
 static int launch_dma_group(const FBatch& b, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;                 // (one per kernel variant; safe from any number of host threads)
+    std::call_once(attr_once, [] {
         (void)hipFuncSetAttribute((const void*)factor_dma_kernel<PLAIN, F16>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, FACTOR_DMA_LDS);
-        attr_set = true;
-    }
+    });
     void* tok = nullptr;
     if (timing_enabled()) timing_begin(PLAIN ? "factor_dma_kernel<plain>" : "factor_dma_kernel<conv>", stream, &tok);
     hipLaunchKernelGGL((factor_dma_kernel<PLAIN, F16>), dim3(b.prefix[b.count]), dim3(256), FACTOR_DMA_LDS, stream, b);

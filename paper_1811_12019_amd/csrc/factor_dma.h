@@ -24,10 +24,7 @@
 namespace kfac {
 
 constexpr int DK = 32;                       // unfolded rows per stage
-#ifndef FACTOR_DNS
-#define FACTOR_DNS 3
-#endif
-constexpr int DNS = FACTOR_DNS;              // stages in the ring (DNS - 1 in flight)
+constexpr int DNS = 3;                       // stages in the ring (DNS - 1 in flight)
 constexpr int DPANEL = 8 * 1024;             // bytes per operand panel per stage
 constexpr int DSTAGE = 2 * DPANEL;
 constexpr int FACTOR_DMA_LDS = DNS * DSTAGE; // 49,152 B (the epilogue staging aliases it)

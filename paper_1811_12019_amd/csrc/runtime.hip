@@ -3,6 +3,7 @@
 // kfac_kernel_timing_report() waits for them and adds up elapsed time and launch count per kernel name.
 // This is a measurement aid for benchmarks: it serialises nothing but adds two event records per launch,
 // so it is never enabled inside a throughput measurement.
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -19,14 +20,14 @@ struct TimedLaunch {
 };
 
 static std::mutex g_mu;
-static bool g_enabled = false;
+static std::atomic<bool> g_enabled{false};
 static std::vector<TimedLaunch> g_launches;
 
-bool timing_enabled() { return g_enabled; }
+bool timing_enabled() { return g_enabled.load(std::memory_order_relaxed); }
 
 void timing_begin(const char* name, hipStream_t stream, void** token) {
     *token = nullptr;
-    if (!g_enabled) return;
+    if (!timing_enabled()) return;
     TimedLaunch* tl = new TimedLaunch;
     tl->name = name;
     if (hipEventCreate(&tl->start) != hipSuccess || hipEventCreate(&tl->stop) != hipSuccess) {
@@ -50,7 +51,7 @@ void timing_end(hipStream_t stream, void* token) {
 
 extern "C" int kfac_kernel_timing_enable(int enable) {
     std::lock_guard<std::mutex> lk(kfac::g_mu);
-    kfac::g_enabled = enable != 0;
+    kfac::g_enabled.store(enable != 0);
     return KFAC_OK;
 }
 

@@ -7,7 +7,7 @@
 
 namespace kfac {
 
-constexpr int WU_MAX = 128;               // layers per launch (argument block under 4 KB)
+constexpr int WU_MAX = 128;               // layers per launch (a 4.6 KB argument block)
 constexpr unsigned WU_CHUNK = 4096;       // elements per workgroup
 
 struct UpdateBatch {

@@ -220,9 +220,38 @@ typedef struct kfac_inverse_item {
     int32_t* info;      /* device status word or NULL                                                     */
     int32_t dim;
     float damping;
+    const float* damping_dev;  /* NULL, or a device float that replaces `damping` (read when the work runs: the
+                                  value may come from kfac_pi_damping_batched enqueued before on the same stream) */
 } kfac_inverse_item;
 
 int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, int32_t count, void* stream);
+
+/* Damping of Sec. 4.2.
+ * The split of a block's damping gamma between its Kronecker factors in proportion to their scale (the factored Tikhonov
+ * damping the section names): lam[2 i] = pi_i sqrt(gamma) for A_i and lam[2 i + 1] = sqrt(gamma) / pi_i for G_i, with
+ * pi_i = sqrt((tr A_i / dA_i) / (tr G_i / dG_i)); pi_i = 1 if a trace is not positive.  lam: 2 * count device floats,
+ * meant to be handed to the inversions through kfac_inverse_item.damping_dev.  One launch per 128 layers; deterministic.
+ * The item array is read on the host during the call. */
+typedef struct kfac_pi_item {
+    const float* A;      /* dA x dA (device): the factor as it will be inverted (the running average) */
+    const float* G;      /* dG x dG (device) */
+    int32_t dA, dG;
+} kfac_pi_item;
+
+int kfac_pi_damping_batched(const kfac_pi_item* items_host, int32_t count, float gamma, float* lam, void* stream);
+
+/* Warm-up damping (Sec. 4.2), host arithmetic on scalars: alpha = 2 log10(gamma0 / gamma_target) / t_warmup (NaN for a
+ * non-positive argument) and gamma(t+1) = (1 - alpha) gamma(t) + alpha gamma_target; the damping of the Batch
+ * Normalization layers is rho_bn * gamma. */
+double kfac_warmup_damping_alpha(double gamma0, double gamma_target, double t_warmup);
+double kfac_warmup_damping_next(double gamma, double gamma_target, double alpha);
+double kfac_bn_damping(double gamma, double rho_bn);
+
+/* Iterations between two refreshes of the statistics in epoch `epoch` (Sec. 5.4, training with stale statistics):
+ * KFAC_REFRESH_GROWING: min(20, 5 floor(epoch / 5) + 1); KFAC_REFRESH_LATE: 1 before epoch 13, 20 from then on.
+ * -1 for a negative epoch or an unknown heuristic.  Host function. */
+enum { KFAC_REFRESH_GROWING = 0, KFAC_REFRESH_LATE = 1 };
+int32_t kfac_refresh_interval(int32_t epoch, int32_t heuristic);
 
 /* Workspace for kfac_precondition (the d_A x d_G intermediate). */
 size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA);

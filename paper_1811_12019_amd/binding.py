@@ -33,6 +33,8 @@ EXPORTED_SYMBOLS = (
     "kfac_bn_sample_grads_workspace_bytes", "kfac_bn_sample_grads", "kfac_bn_diag_precondition",
     "kfac_bn_sample_grads_batched_workspace_bytes", "kfac_bn_sample_grads_batched",
     "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
+    "kfac_pi_damping_batched", "kfac_warmup_damping_alpha", "kfac_warmup_damping_next", "kfac_bn_damping",
+    "kfac_refresh_interval",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
     "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
 )
@@ -76,7 +78,11 @@ class kfac_update_item(ctypes.Structure):
 
 class kfac_inverse_item(ctypes.Structure):
     _fields_ = [("S", ctypes.c_void_p), ("Minv", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("info", ctypes.c_void_p),
-                ("dim", ctypes.c_int32), ("damping", ctypes.c_float)]
+                ("dim", ctypes.c_int32), ("damping", ctypes.c_float), ("damping_dev", ctypes.c_void_p)]
+
+
+class kfac_pi_item(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("G", ctypes.c_void_p), ("dA", ctypes.c_int32), ("dG", ctypes.c_int32)]
 
 
 class kfac_precond_item(ctypes.Structure):
@@ -148,6 +154,17 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_damped_inverse.argtypes = [vp, i32, f32, vp, vp, vp, sz, vp]
     lib.kfac_damped_inverse_batched.restype = ctypes.c_int
     lib.kfac_damped_inverse_batched.argtypes = [itemp, i32, vp]
+    lib.kfac_pi_damping_batched.restype = ctypes.c_int
+    lib.kfac_pi_damping_batched.argtypes = [ctypes.POINTER(kfac_pi_item), i32, f32, vp, vp]
+    f64 = ctypes.c_double
+    lib.kfac_warmup_damping_alpha.restype = f64
+    lib.kfac_warmup_damping_alpha.argtypes = [f64, f64, f64]
+    lib.kfac_warmup_damping_next.restype = f64
+    lib.kfac_warmup_damping_next.argtypes = [f64, f64, f64]
+    lib.kfac_bn_damping.restype = f64
+    lib.kfac_bn_damping.argtypes = [f64, f64]
+    lib.kfac_refresh_interval.restype = i32
+    lib.kfac_refresh_interval.argtypes = [i32, i32]
     lib.kfac_precondition_workspace_bytes.restype = sz
     lib.kfac_precondition_workspace_bytes.argtypes = [i32, i32]
     lib.kfac_precondition.restype = ctypes.c_int
@@ -428,7 +445,9 @@ class InverseBatch:
     """A kfac_inverse_item table (host memory; built once, reused every step) and the scratch it points to."""
 
     def __init__(self, S: Sequence[torch.Tensor], Minv: Sequence[torch.Tensor], dampings: Sequence[float],
-                 info: Optional[torch.Tensor] = None, device="cuda"):
+                 info: Optional[torch.Tensor] = None, device="cuda",
+                 dampings_dev: Optional[Sequence[Optional[int]]] = None):
+        """dampings_dev[i]: None, or the device address of a float that replaces dampings[i] when the work runs."""
         n = len(S)
         dims = [int(s.shape[0]) for s in S]
         self.order = sorted(range(n), key=lambda i: -dims[i])        # the ABI wants largest first
@@ -439,13 +458,57 @@ class InverseBatch:
         arr = (kfac_inverse_item * n)()
         for slot, i in enumerate(self.order):
             arr[slot] = kfac_inverse_item(S[i].data_ptr(), Minv[i].data_ptr(), _ptr(self.ws[i]),
-                                          self.info.data_ptr() + 4 * i, dims[i], float(dampings[i]))
+                                          self.info.data_ptr() + 4 * i, dims[i], float(dampings[i]),
+                                          None if dampings_dev is None else dampings_dev[i])
         self.host = arr
 
 
 def kfac_damped_inverse_batched(batch: InverseBatch, stream=None) -> None:
     rc = load_library().kfac_damped_inverse_batched(batch.host, batch.count, _stream(stream))
     _check(rc, "kfac_damped_inverse_batched")
+
+
+KFAC_REFRESH_GROWING, KFAC_REFRESH_LATE = 0, 1
+
+
+class PiBatch:
+    """A kfac_pi_item table (host memory) and the device array of per-factor dampings it fills: lam[2 i] for A_i,
+    lam[2 i + 1] for G_i."""
+
+    def __init__(self, A: Sequence[torch.Tensor], G: Sequence[torch.Tensor], device="cuda"):
+        n = len(A)
+        self.count = n
+        self.keep = (list(A), list(G))
+        self.host = (kfac_pi_item * max(n, 1))()
+        for i in range(n):
+            self.host[i] = kfac_pi_item(A[i].data_ptr(), G[i].data_ptr(), int(A[i].shape[0]), int(G[i].shape[0]))
+        self.lam = torch.zeros(2 * max(n, 1), dtype=torch.float32, device=device)
+
+    def address(self, layer: int, which: int) -> int:
+        """Device address of lambda_A (which = 0) or lambda_G (which = 1) of a layer."""
+        return self.lam.data_ptr() + 4 * (2 * layer + which)
+
+
+def kfac_pi_damping_batched(batch: PiBatch, gamma: float, stream=None) -> torch.Tensor:
+    rc = load_library().kfac_pi_damping_batched(batch.host, batch.count, float(gamma), _ptr(batch.lam), _stream(stream))
+    _check(rc, "kfac_pi_damping_batched")
+    return batch.lam[:2 * batch.count]
+
+
+def kfac_warmup_damping_alpha(gamma0: float, gamma_target: float, t_warmup: float) -> float:
+    return float(load_library().kfac_warmup_damping_alpha(float(gamma0), float(gamma_target), float(t_warmup)))
+
+
+def kfac_warmup_damping_next(gamma: float, gamma_target: float, alpha: float) -> float:
+    return float(load_library().kfac_warmup_damping_next(float(gamma), float(gamma_target), float(alpha)))
+
+
+def kfac_bn_damping(gamma: float, rho_bn: float) -> float:
+    return float(load_library().kfac_bn_damping(float(gamma), float(rho_bn)))
+
+
+def kfac_refresh_interval(epoch: int, heuristic: int = KFAC_REFRESH_GROWING) -> int:
+    return int(load_library().kfac_refresh_interval(int(epoch), int(heuristic)))
 
 
 def kfac_precondition_workspace_bytes(dG: int, dA: int) -> int:

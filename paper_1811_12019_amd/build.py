@@ -8,7 +8,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libkfac_hip.so")
-SOURCES = ["factor.hip", "ema.hip", "packed.hip", "diff.hip", "update.hip", "bn.hip", "inverse.hip", "precondition.hip", "runtime.hip"]
+SOURCES = ["factor.hip", "ema.hip", "packed.hip", "diff.hip", "update.hip", "bn.hip", "inverse.hip", "damping.hip", "precondition.hip", "runtime.hip"]
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops

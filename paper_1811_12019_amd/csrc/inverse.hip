@@ -45,11 +45,14 @@ struct Batch {
     int dim[MAXB];
     int step[MAXB];                   // the elimination step this launch takes for the matrix, or -1: none
     float damping[MAXB];
+    const float* damping_dev[MAXB];   // NULL, or where the damping is to be read from instead
     const float* S[MAXB];
     float* Minv[MAXB];
     void* ws[MAXB];
     int32_t* info[MAXB];
 };
+
+static_assert(sizeof(Batch) <= 4096, "the batch travels in the kernel arguments");
 
 // One matrix of the batch as the kernels see it: pointers typed as global memory.
 struct Item {
@@ -68,7 +71,7 @@ __device__ __forceinline__ Item get_item(const Batch& b, int m) {
     it.ws = as_global((float*)b.ws[m]);
     it.info = as_global((int*)b.info[m]);
     it.dim = b.dim[m];
-    it.damping = b.damping[m];
+    it.damping = b.damping_dev[m] ? *as_global(b.damping_dev[m]) : b.damping[m];
     return it;
 }
 
@@ -1211,6 +1214,7 @@ static void fill_batch(Batch& b, const kfac_inverse_item* items, int count) {
     for (int i = 0; i < count; ++i) {
         b.dim[i] = items[i].dim;
         b.damping[i] = items[i].damping;
+        b.damping_dev[i] = items[i].damping_dev;
         b.S[i] = items[i].S;
         b.Minv[i] = items[i].Minv;
         b.ws[i] = items[i].ws;
@@ -1291,7 +1295,7 @@ extern "C" size_t kfac_inverse_workspace_bytes(int32_t dim) {
 extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, float* Minv, int32_t* info,
                                    void* ws, size_t ws_bytes, void* stream) {
     kfac_inverse_item it;
-    it.S = S; it.Minv = Minv; it.ws = ws; it.info = info; it.dim = dim; it.damping = damping;
+    it.S = S; it.Minv = Minv; it.ws = ws; it.info = info; it.dim = dim; it.damping = damping; it.damping_dev = nullptr;
     if (dim <= 0 || dim > 32768 || !S || !Minv || S == Minv) return KFAC_ERR_INVALID_ARG;
     if (nblk_of(dim) > 1) {
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < ws_bytes_of(dim)) return KFAC_ERR_WORKSPACE;

@@ -1,7 +1,8 @@
 """Whole-network K-FAC step on one GPU: owns the device buffers of every layer and enqueues the C-ABI
 calls in the order of Algorithm 1 (stages 1, 2, 4, 5) for all layers locally.
 
-No arithmetic happens here: every number is produced by the HIP library.  torch is used for device
+No arithmetic of the method happens here: every number is produced by the HIP library (the schedules of Sec. 4.2 and
+5.4 are host functions of the library too: binding.kfac_warmup_damping_*, binding.kfac_refresh_interval).  torch is used for device
 memory, seeded synthetic inputs and the stream.
 """
 from __future__ import annotations
@@ -51,7 +52,7 @@ INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
 class _Wave:
     """A subset of the layers with batched-call tables of its own."""
 
-    def __init__(self, layers: List[LayerState], decay, damping: float, n_groups: int, device):
+    def __init__(self, layers: List[LayerState], decay, damping: float, n_groups: int, device, pi_split: bool = False):
         self.layers = layers
         builds = []
         for l in layers:
@@ -66,6 +67,10 @@ class _Wave:
         for l in layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
             dst += [l.A_inv, l.G_inv]
+        # trace-ratio split of the damping between a layer's factors: computed on the device before the inversions,
+        # which read their damping from there
+        self.pi_batch = kb.PiBatch(src[0::2], src[1::2], device=device) if pi_split else None
+        lam_dev = ([self.pi_batch.address(i // 2, i % 2) for i in range(len(src))] if pi_split else None)
         # The inversions are independent, so they are dealt (largest first, to the least loaded group, by d^3) into a
         # few groups that run on streams of their own: the latency-bound pivot / panel kernels of one group then
         # overlap with the throughput-bound updates of the others.  (Grouping by block count instead, so that a
@@ -78,7 +83,8 @@ class _Wave:
             groups[g].append(i)
             load[g] += float(src[i].shape[0]) ** 3
         self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [damping] * len(grp),
-                                            device=device)
+                                            device=device,
+                                            dampings_dev=None if lam_dev is None else [lam_dev[i] for i in grp])
                             for grp in groups if grp]
 
 
@@ -95,15 +101,17 @@ class KfacNetworkStep:
 
     def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
                  decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda",
-                 inverse_streams: int = 3, long_dim: int = 2048):
+                 inverse_streams: int = 3, long_dim: int = 2048, pi_split: bool = False):
         self.decay = decay
+        self.gamma = float(gamma)
+        self.pi_split = pi_split                     # False: sqrt(gamma) on each factor; True: the trace-ratio split
         self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
         self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
-        self.all = _Wave(self.layers, decay, self.damping, inverse_streams, device)
+        self.all = _Wave(self.layers, decay, self.damping, inverse_streams, device, pi_split)
         long_ = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) >= long_dim]
         short = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) < long_dim]
-        self.waves = ([_Wave(long_, decay, self.damping, inverse_streams, device),
-                       _Wave(short, decay, self.damping, 1, device)] if long_ and short else [])
+        self.waves = ([_Wave(long_, decay, self.damping, inverse_streams, device, pi_split),
+                       _Wave(short, decay, self.damping, 1, device, pi_split)] if long_ and short else [])
         self.inv_streams = [torch.cuda.Stream(device=device) for _ in range(max(1, inverse_streams))]
         self.overlap_inversions = True      # False: run the groups one after the other on the caller's stream
         self.pipelined = True               # False: step() runs stage after stage
@@ -116,6 +124,10 @@ class KfacNetworkStep:
         if self.decay is None:
             return
         kb.kfac_ema_batched(self.all.ema_batch, self.decay, stream)
+
+    def _split_damping(self, wave, stream):
+        if wave.pi_batch is not None:
+            kb.kfac_pi_damping_batched(wave.pi_batch, self.gamma, stream)
 
     @staticmethod
     def _fork(batches, sides, main):
@@ -134,6 +146,7 @@ class KfacNetworkStep:
     def invert(self, stream=None):
         main = torch.cuda.current_stream() if stream is None else stream
         batches = self.all.inv_batches
+        self._split_damping(self.all, main)
         if not self.overlap_inversions or len(batches) == 1:
             for batch in batches:
                 kb.kfac_damped_inverse_batched(batch, main)
@@ -166,10 +179,12 @@ class KfacNetworkStep:
         kb.kfac_factor_batched(lw.factor_batch, main)
         if self.decay is not None:
             kb.kfac_ema_batched(lw.ema_batch, self.decay, main)
+        self._split_damping(lw, main)
         joins = self._fork(lw.inv_batches, self.inv_streams, main)
         kb.kfac_factor_batched(sw.factor_batch, main)
         if self.decay is not None:
             kb.kfac_ema_batched(sw.ema_batch, self.decay, main)
+        self._split_damping(sw, main)
         for batch in sw.inv_batches:
             kb.kfac_damped_inverse_batched(batch, main)
         kb.kfac_precondition_batched(sw.pre_batch, main)
@@ -181,30 +196,6 @@ class KfacNetworkStep:
         for l in self.layers:
             l.A_run.copy_(torch.eye(l.shape.d_A, device=l.A_run.device))
             l.G_run.copy_(torch.eye(l.shape.d_G, device=l.G_run.device))
-
-
-def refresh_interval(epoch: int) -> int:
-    """Iterations between refreshes of the statistics in epoch e (Sec. 5.4, first heuristic): min(20, 5 floor(e/5) + 1)."""
-    return min(20, 5 * (int(epoch) // 5) + 1)
-
-
-def refresh_interval_late(epoch: int) -> int:
-    """Second heuristic of Sec. 5.4: every iteration before epoch 13, every 20th afterwards."""
-    return 1 if int(epoch) < 13 else 20
-
-
-def learning_rate(epoch: float, eta0: float, e_start: float, e_end: float, p_decay: float) -> float:
-    """Polynomial decay of Sec. 4.3 (eta0 before e_start, 0 after e_end)."""
-    if epoch <= e_start:
-        return float(eta0)
-    if epoch >= e_end:
-        return 0.0
-    return float(eta0) * (1.0 - (epoch - e_start) / (e_end - e_start)) ** p_decay
-
-
-def momentum_rate(eta: float, eta0: float, m0: float) -> float:
-    """m(e) = m0 / eta0 * eta(e) (Sec. 4.3)."""
-    return float(m0) / float(eta0) * float(eta)
 
 
 # Algorithmic work, for rooflines (2 flops per multiply-add; symmetric outputs counted as a triangle).

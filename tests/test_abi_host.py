@@ -34,7 +34,7 @@ def test_status_strings():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(kb.kfac_layer_desc) == 13 * 4
-    assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8
+    assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8 + 8
     assert ctypes.sizeof(kb.kfac_precond_item) == 5 * 8 + 8
     assert ctypes.sizeof(kb.kfac_factor_item) == 56 + 4 * 8 + 8
 
@@ -135,8 +135,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_damped_inverse(fake, 300, 0.1, ctypes.c_void_p(0x90000), None, None, 0, None) == kb.KFAC_ERR_WORKSPACE
 
     items = (kb.kfac_inverse_item * 2)()
-    items[0] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 64, 0.1)
-    items[1] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 300, 0.1)       # not sorted largest-first
+    items[0] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 64, 0.1, None)
+    items[1] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 300, 0.1, None)       # not sorted largest-first
     assert lib.kfac_damped_inverse_batched(items, 2, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse_batched(items, 0, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse_batched(None, 1, None) == kb.KFAC_ERR_INVALID_ARG
@@ -162,13 +162,32 @@ def test_product_does_not_import_the_oracle():
     assert "paper_1811_12019_amd" not in ora and "ctypes" not in ora
 
 
-def test_refresh_interval_helpers_match_the_paper_formulas():
-    from oracle import kfac_oracle as ko
-    from paper_1811_12019_amd import step as kstep
-    for e in range(0, 60):
-        assert kstep.refresh_interval(e) == ko.refresh_interval(e)
-        assert kstep.refresh_interval_late(e) == ko.refresh_interval_late(e)
-    for e in (0.0, 1.0, 2.5, 17.3, 34.9, 35.0, 40.0):
-        eta = kstep.learning_rate(e, 8.18e-3, 1.0, 35.0, 3.5)
-        assert eta == ko.learning_rate(e, 8.18e-3, 1.0, 35.0, 3.5)
-        assert kstep.momentum_rate(eta, 8.18e-3, 0.997) == ko.momentum_rate(eta, 8.18e-3, 0.997)
+def test_schedule_host_functions_against_hand_worked_values():
+    """The host functions of Sec. 4.2 (warm-up damping) and Sec. 5.4 (refresh intervals) against values worked by hand
+    from the paper's formulas and its Table 3 (not against the oracle's text)."""
+    # interval(e) = min(20, 5 floor(e / 5) + 1): 1 for epochs 0-4, 6 for 5-9, 11, 16, then 20 from epoch 20 on
+    want = {0: 1, 4: 1, 5: 6, 9: 6, 10: 11, 14: 11, 15: 16, 19: 16, 20: 20, 21: 20, 44: 20}
+    for e, v in want.items():
+        assert kb.kfac_refresh_interval(e, kb.KFAC_REFRESH_GROWING) == v
+    # second heuristic: every step before epoch 13, every 20th afterwards
+    for e, v in {0: 1, 12: 1, 13: 20, 40: 20}.items():
+        assert kb.kfac_refresh_interval(e, kb.KFAC_REFRESH_LATE) == v
+    assert kb.kfac_refresh_interval(-1, 0) == -1 and kb.kfac_refresh_interval(3, 7) == -1
+    # Table 3, BS 4,096: gamma0 = 2.5e-2 = 100 gamma_target, t_warmup = 313 -> alpha = 2 * 2 / 313
+    alpha = kb.kfac_warmup_damping_alpha(2.5e-2, 2.5e-4, 313)
+    assert alpha == pytest.approx(4.0 / 313.0, rel=1e-14)
+    assert kb.kfac_warmup_damping_next(2.5e-2, 2.5e-4, alpha) == pytest.approx(0.025 - 0.02475 * 4.0 / 313.0, rel=1e-14)
+    assert kb.kfac_warmup_damping_next(2.5e-4, 2.5e-4, alpha) == pytest.approx(2.5e-4, rel=1e-14)
+    assert kb.kfac_warmup_damping_alpha(0.0, 1.0, 10) != kb.kfac_warmup_damping_alpha(0.0, 1.0, 10)     # NaN
+    assert kb.kfac_bn_damping(2.5e-4, 16.0) == pytest.approx(4.0e-3)
+
+
+def test_pi_damping_arguments():
+    lib = kb.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    items = (kb.kfac_pi_item * 1)(kb.kfac_pi_item(0x1000, 0x2000, 5, 0))          # dG = 0
+    assert lib.kfac_pi_damping_batched(items, 1, 1e-3, fake, None) == kb.KFAC_ERR_INVALID_ARG
+    items[0] = kb.kfac_pi_item(0x1000, 0x2000, 5, 3)
+    assert lib.kfac_pi_damping_batched(items, 1, -1.0, fake, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_pi_damping_batched(items, 1, 1e-3, None, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_pi_damping_batched(items, 0, 1e-3, None, None) == kb.KFAC_OK

@@ -130,6 +130,12 @@ def test_factors_narrow_layers(shape, dtype):
     check_factor_pair(shape, kb.KFAC_NHWC, dtype, kb.KFAC_ORDER_KH_KW_C, seed=3)
 
 
+def test_factor_image_too_wide_for_the_packed_patch_origin():
+    """An image wider than the matrix-core kernel's 16-bit patch coordinates allow is served by another kernel."""
+    shp = synth.LayerShape("wide", 1, 8, 3, 17000, 8, 3, 3, 1, 1)
+    check_factor_pair(shp, kb.KFAC_NHWC, kb.KFAC_BF16, kb.KFAC_ORDER_KH_KW_C)
+
+
 def test_factor_batched_matches_single_calls():
     """A mixed batch (1x1, 3x3, strided, fc, a layer only the generic kernel serves) equals the single calls bit for bit."""
     shapes = [SMALL_SHAPES[0], SMALL_SHAPES[1], SMALL_SHAPES[3], SMALL_SHAPES[4], SMALL_SHAPES[5], SMALL_SHAPES[2]]
@@ -566,6 +572,36 @@ def test_damped_inverse_batched_more_matrices_than_one_launch_group():
             np.testing.assert_array_equal(single, got)
 
 
+def test_pi_damping_split_and_device_side_damping():
+    """Trace-ratio split of the damping on the device (Sec. 4.2), and inversions that read their damping from there."""
+    dims = [(145, 16), (577, 64), (64, 300), (1, 1)]
+    rng = np.random.default_rng(31)
+    As = [synth.random_spd(a, seed=40 + i) * np.float32(10.0 ** (i - 1)) for i, (a, g) in enumerate(dims)]
+    Gs = [synth.random_spd(g, seed=50 + i) * np.float32(0.01) for i, (a, g) in enumerate(dims)]
+    At = [torch.from_numpy(x).to(DEV) for x in As]
+    Gt = [torch.from_numpy(x).to(DEV) for x in Gs]
+    gamma = 1e-3
+    pi = kb.PiBatch(At, Gt, device=DEV)
+    lam = kb.kfac_pi_damping_batched(pi, gamma)
+    torch.cuda.synchronize()
+    lam = lam.cpu().numpy()
+    for i in range(len(dims)):
+        la, lg = ko.factor_damping_pi(As[i], Gs[i], gamma)
+        assert lam[2 * i] == pytest.approx(la, rel=2e-6) and lam[2 * i + 1] == pytest.approx(lg, rel=2e-6)
+    # the inversions read lambda from the device array (the host value, deliberately wrong, must be ignored)
+    S = At + Gt
+    Mt = [torch.full_like(x, float("nan")) for x in S]
+    addr = [pi.address(i, 0) for i in range(len(dims))] + [pi.address(i, 1) for i in range(len(dims))]
+    batch = kb.InverseBatch(S, Mt, [123.0] * len(S), device=DEV, dampings_dev=addr)
+    kb.kfac_damped_inverse_batched(batch)
+    torch.cuda.synchronize()
+    assert batch.info.cpu().tolist() == [0] * len(S)
+    lams = [lam[2 * i] for i in range(len(dims))] + [lam[2 * i + 1] for i in range(len(dims))]
+    for x, l, m in zip(As + Gs, lams, Mt):
+        ref = ko.damped_inverse(x, float(l))
+        assert rel_fro(m.cpu().numpy(), ref) < INV_TOL and rel_max(m.cpu().numpy(), ref) < INV_TOL
+
+
 # ----------------------------------------------------------------------------------------------
 # preconditioning
 # ----------------------------------------------------------------------------------------------
@@ -672,6 +708,25 @@ NET_LAYERS = [
 # stage-wise): 2e-3 bounds the preconditioned gradient against the all-float64 chain.  Stage by stage, each against
 # the oracle fed the GPU stage's own input, the bars are the usual ones.
 END_TO_END_TOL = 2e-3
+
+
+@pytest.mark.parametrize("long_dim", [2048, 140])
+def test_network_step_with_trace_ratio_damping(long_dim):
+    """One step of the small network with the damping split by the trace ratio of each layer's factors (computed on the
+    device between the running averages and the inversions), in both schedules."""
+    from paper_1811_12019_amd import step as kstep
+    gamma = 1e-3
+    net = kstep.KfacNetworkStep(NET_LAYERS, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=0.95, gamma=gamma,
+                                seed=5, device=DEV, inverse_streams=2, long_dim=long_dim, pi_split=True)
+    net.step()
+    torch.cuda.synchronize()
+    assert int(net.inverse_info().abs().max()) == 0
+    f64 = lambda t: t.detach().cpu().numpy().astype(np.float64)
+    for l in net.layers:
+        la, lg = ko.factor_damping_pi(f64(l.A_run), f64(l.G_run), gamma)
+        assert rel_fro(f64(l.A_inv), ko.damped_inverse(f64(l.A_run), float(np.float32(la)))) < INV_TOL, l.shape.name
+        assert rel_fro(f64(l.G_inv), ko.damped_inverse(f64(l.G_run), float(np.float32(lg)))) < INV_TOL, l.shape.name
+        assert rel_fro(f64(l.P), ko.precondition(f64(l.G_inv), f64(l.gradW), f64(l.A_inv))) < PRE_TOL
 
 
 @pytest.mark.parametrize("long_dim", [2048, 140])

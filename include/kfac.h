@@ -43,7 +43,8 @@ typedef enum kfac_status {
     KFAC_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent descriptor            */
     KFAC_ERR_UNSUPPORTED = -2,   /* valid request this build has no kernel for                           */
     KFAC_ERR_WORKSPACE = -3,     /* ws is NULL / misaligned / smaller than *_workspace_bytes says         */
-    KFAC_ERR_HIP = -4            /* a HIP runtime call (launch, memset) failed                            */
+    KFAC_ERR_HIP = -4,           /* a HIP runtime call (launch, memset) failed                            */
+    KFAC_ERR_TOO_LARGE = -5      /* more work than the fixed scratch of a *_noalloc entry point can hold   */
 } kfac_status;
 
 typedef enum kfac_dtype { KFAC_F32 = 0, KFAC_BF16 = 1, KFAC_F16 = 2 } kfac_dtype;
@@ -153,6 +154,17 @@ typedef struct kfac_diff_item {
 size_t kfac_factor_diff_workspace_bytes(const kfac_diff_item* items_host, int32_t count);
 int kfac_factor_diff_batched(const kfac_diff_item* items_host, int32_t count, float* out, void* ws, size_t ws_bytes,
                              void* stream);
+
+/* The same computation for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The chunk sums go to a fixed 1 MiB array inside the
+ * library's device image instead of `ws`; the call allocates and frees nothing.  Limit: the matrices' chunk counts
+ * (ceil(dim^2 / 8192) each) may add up to at most 65536, i.e. kfac_factor_diff_noalloc_max_elements() = 2^29 elements
+ * when every matrix fills its chunks; beyond it the call returns KFAC_ERR_TOO_LARGE and launches nothing.  All calls on
+ * one GPU share the array: calls that overlap in time on one GPU (different streams or threads) race and must be
+ * serialised by the caller.  Nothing in it needs clearing between calls (every entry is written before it is read).
+ * Results are bit-identical to kfac_factor_diff_batched. */
+int kfac_factor_diff_batched_noalloc(const kfac_diff_item* items_host, int32_t count, float* out, void* stream);
+size_t kfac_factor_diff_noalloc_max_elements(void);
 
 /* Optimizer tail for `count` layers: w_next = w - eta * precond + momentum * (w - w_prev)  (Sec. 4.3, the update
  * equation), then w_next <- sqrt(2 d_out) * w_next / (||w_next|| + eps)  (Sec. 4.4, weights rescaling; the norm is over

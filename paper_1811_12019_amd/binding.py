@@ -19,7 +19,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libkfac_hip.so")
 
 KFAC_OK = 0
-KFAC_ERR_INVALID_ARG, KFAC_ERR_UNSUPPORTED, KFAC_ERR_WORKSPACE, KFAC_ERR_HIP = -1, -2, -3, -4
+KFAC_ERR_INVALID_ARG, KFAC_ERR_UNSUPPORTED, KFAC_ERR_WORKSPACE, KFAC_ERR_HIP, KFAC_ERR_TOO_LARGE = -1, -2, -3, -4, -5
 KFAC_F32, KFAC_BF16, KFAC_F16 = 0, 1, 2
 KFAC_NCHW, KFAC_NHWC = 0, 1
 KFAC_ORDER_C_KH_KW, KFAC_ORDER_KH_KW_C = 0, 1
@@ -28,7 +28,8 @@ KFAC_OP_FACTOR_A, KFAC_OP_FACTOR_G = 0, 1
 EXPORTED_SYMBOLS = (
     "kfac_status_string", "kfac_factor_workspace_bytes", "kfac_factor_A", "kfac_factor_G", "kfac_factor_batched",
     "kfac_ema", "kfac_ema_batched", "kfac_pack_upper_batched", "kfac_ema_packed_batched",
-    "kfac_factor_diff_workspace_bytes", "kfac_factor_diff_batched",
+    "kfac_factor_diff_workspace_bytes", "kfac_factor_diff_batched", "kfac_factor_diff_batched_noalloc",
+    "kfac_factor_diff_noalloc_max_elements",
     "kfac_weight_update_workspace_bytes", "kfac_weight_update_batched",
     "kfac_bn_sample_grads_workspace_bytes", "kfac_bn_sample_grads", "kfac_bn_diag_precondition",
     "kfac_bn_sample_grads_batched_workspace_bytes", "kfac_bn_sample_grads_batched",
@@ -134,6 +135,10 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_factor_diff_workspace_bytes.argtypes = [ctypes.POINTER(kfac_diff_item), i32]
     lib.kfac_factor_diff_batched.restype = ctypes.c_int
     lib.kfac_factor_diff_batched.argtypes = [ctypes.POINTER(kfac_diff_item), i32, vp, vp, sz, vp]
+    lib.kfac_factor_diff_batched_noalloc.restype = ctypes.c_int
+    lib.kfac_factor_diff_batched_noalloc.argtypes = [ctypes.POINTER(kfac_diff_item), i32, vp, vp]
+    lib.kfac_factor_diff_noalloc_max_elements.restype = sz
+    lib.kfac_factor_diff_noalloc_max_elements.argtypes = []
     lib.kfac_weight_update_workspace_bytes.restype = sz
     lib.kfac_weight_update_workspace_bytes.argtypes = [ctypes.POINTER(kfac_update_item), i32]
     lib.kfac_weight_update_batched.restype = ctypes.c_int
@@ -346,6 +351,17 @@ def kfac_factor_diff_batched(batch: DiffBatch, stream=None) -> torch.Tensor:
                                                  _stream(stream))
     _check(rc, "kfac_factor_diff_batched")
     return batch.out[:batch.count]
+
+
+def kfac_factor_diff_batched_noalloc(items_host, count: int, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """The same computation with the library's fixed scratch: nothing is allocated (items_host: a kfac_diff_item array)."""
+    rc = load_library().kfac_factor_diff_batched_noalloc(items_host, int(count), _ptr(out), _stream(stream))
+    _check(rc, "kfac_factor_diff_batched_noalloc")
+    return out
+
+
+def kfac_factor_diff_noalloc_max_elements() -> int:
+    return int(load_library().kfac_factor_diff_noalloc_max_elements())
 
 
 class UpdateBatch:

@@ -2,6 +2,8 @@
 // Fisher information"), for many matrices in one call.  HBM bound: 8 bytes per element, each read once.
 // Two deterministic passes: every workgroup reduces one 8192-element chunk of one matrix to a (numerator,
 // denominator) pair of doubles in the caller's scratch; one workgroup per matrix then adds its pairs in a fixed order.
+#include <mutex>
+
 #include "common.h"
 
 namespace kfac {
@@ -83,6 +85,63 @@ __global__ __launch_bounds__(256) void diff_final_kernel(DiffBatch b, const doub
 
 static unsigned chunks_of(int dim) { return (unsigned)(((size_t)dim * dim + DF_CHUNK - 1) / DF_CHUNK); }
 
+// Scratch of the entry point that allocates nothing: room for the chunk pairs of 2^29 matrix elements (2 GiB of fp32
+// factors; all 108 factors of ResNet-50 are 0.15 x 2^30 elements), 1 MiB per GPU the library runs on, held until the
+// process ends.  In host code the array's name only stands for the symbol: its device address is looked up once per
+// device (static_scratch) and that pointer is what the kernels get.
+constexpr size_t DF_STATIC_CHUNKS = 65536;
+static __device__ __align__(256) double scratch[2 * DF_STATIC_CHUNKS];
+
+constexpr int DF_MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static double* g_scratch_ptr[DF_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, or nullptr if it cannot be had.
+static double* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= DF_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = (double*)p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+static int diff_check(const kfac_diff_item* items_host, int32_t count, const float* out) {
+    if (!items_host || count < 0) return KFAC_ERR_INVALID_ARG;
+    if (count == 0) return KFAC_OK;
+    if (!out) return KFAC_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        if (!items_host[i].x || !items_host[i].x_prev || items_host[i].dim <= 0 || items_host[i].dim > 32768)
+            return KFAC_ERR_INVALID_ARG;
+    return KFAC_OK;
+}
+
+// Both passes for all matrices; partial: 2 doubles per chunk, device memory.
+static int diff_run(const kfac_diff_item* items_host, int32_t count, float* out, double* partial, hipStream_t stream) {
+    for (int first = 0; first < count; first += DF_MAX) {
+        const int cnt = count - first < DF_MAX ? count - first : DF_MAX;
+        DiffBatch b;
+        b.count = cnt;
+        unsigned chunks = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const kfac_diff_item& it = items_host[first + i];
+            b.prefix[i] = chunks;
+            b.n[i] = (unsigned long long)it.dim * it.dim;
+            b.x[i] = it.x;
+            b.x_prev[i] = it.x_prev;
+            chunks += chunks_of(it.dim);
+        }
+        b.prefix[cnt] = chunks;
+        KFAC_LAUNCH(diff_partial_kernel, dim3(chunks), dim3(256), stream, b, partial);
+        KFAC_LAUNCH(diff_final_kernel, dim3(cnt), dim3(256), stream, b, (const double*)partial, out + first);
+        partial += 2 * (size_t)chunks;
+    }
+    return KFAC_OK;
+}
+
 }  // namespace kfac
 
 using namespace kfac;
@@ -99,31 +158,21 @@ extern "C" size_t kfac_factor_diff_workspace_bytes(const kfac_diff_item* items_h
 
 extern "C" int kfac_factor_diff_batched(const kfac_diff_item* items_host, int32_t count, float* out, void* ws,
                                         size_t ws_bytes, void* stream) {
-    if (!items_host || count < 0) return KFAC_ERR_INVALID_ARG;
-    if (count == 0) return KFAC_OK;
-    if (!out) return KFAC_ERR_INVALID_ARG;
-    for (int i = 0; i < count; ++i)
-        if (!items_host[i].x || !items_host[i].x_prev || items_host[i].dim <= 0 || items_host[i].dim > 32768)
-            return KFAC_ERR_INVALID_ARG;
+    const int rc = diff_check(items_host, count, out);
+    if (rc != KFAC_OK || count == 0) return rc;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < kfac_factor_diff_workspace_bytes(items_host, count)) return KFAC_ERR_WORKSPACE;
-    double* partial = (double*)ws;
-    for (int first = 0; first < count; first += DF_MAX) {
-        const int cnt = count - first < DF_MAX ? count - first : DF_MAX;
-        DiffBatch b;
-        b.count = cnt;
-        unsigned chunks = 0;
-        for (int i = 0; i < cnt; ++i) {
-            const kfac_diff_item& it = items_host[first + i];
-            b.prefix[i] = chunks;
-            b.n[i] = (unsigned long long)it.dim * it.dim;
-            b.x[i] = it.x;
-            b.x_prev[i] = it.x_prev;
-            chunks += chunks_of(it.dim);
-        }
-        b.prefix[cnt] = chunks;
-        KFAC_LAUNCH(diff_partial_kernel, dim3(chunks), dim3(256), (hipStream_t)stream, b, partial);
-        KFAC_LAUNCH(diff_final_kernel, dim3(cnt), dim3(256), (hipStream_t)stream, b, (const double*)partial, out + first);
-        partial += 2 * (size_t)chunks;
-    }
-    return KFAC_OK;
+    return diff_run(items_host, count, out, (double*)ws, (hipStream_t)stream);
 }
+
+extern "C" int kfac_factor_diff_batched_noalloc(const kfac_diff_item* items_host, int32_t count, float* out, void* stream) {
+    const int rc = diff_check(items_host, count, out);
+    if (rc != KFAC_OK || count == 0) return rc;
+    size_t chunks = 0;
+    for (int i = 0; i < count; ++i) chunks += chunks_of(items_host[i].dim);
+    if (chunks > DF_STATIC_CHUNKS) return KFAC_ERR_TOO_LARGE;
+    double* partial = static_scratch();
+    if (!partial) return KFAC_ERR_HIP;
+    return diff_run(items_host, count, out, partial, (hipStream_t)stream);
+}
+
+extern "C" size_t kfac_factor_diff_noalloc_max_elements(void) { return DF_STATIC_CHUNKS * (size_t)DF_CHUNK; }

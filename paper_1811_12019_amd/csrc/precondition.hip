@@ -152,6 +152,7 @@ extern "C" const char* kfac_status_string(int status) {
         case KFAC_ERR_UNSUPPORTED: return "unsupported";
         case KFAC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case KFAC_ERR_HIP: return "HIP runtime error";
+        case KFAC_ERR_TOO_LARGE: return "request exceeds the fixed scratch of the no-allocation entry point";
         default: return "unknown status";
     }
 }

@@ -91,7 +91,8 @@ int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, float scale, fl
 /* Many factor builds at once (all layers of a network): builds that the matrix-core kernel can serve share a
  * launch, so that the many small ones fill the machine together.  items_host[i] / items_dev[i] describe the same
  * build (device copy uploaded once by the caller); each item's `ws` needs kfac_factor_workspace_bytes(op, &desc)
- * bytes of its own.  Results are identical to the single calls. */
+ * bytes of its own.  Results are identical to the single calls.  An item may instead fold its result into a running
+ * average (`running`) or deliver it as a packed upper triangle (`packed`); see the fields. */
 typedef struct kfac_factor_item {
     kfac_layer_desc desc;
     const void* x;       /* act (op = KFAC_OP_FACTOR_A) or gout (op = KFAC_OP_FACTOR_G), device */
@@ -100,6 +101,12 @@ typedef struct kfac_factor_item {
     size_t ws_bytes;
     float scale;         /* 0 selects 1/R */
     int32_t op;
+    float* running;      /* NULL, or the factor's running average S (d x d, device): the build then ends with
+                            S <- decay S + (1 - decay) factor in its own epilogue (S is read and written once; the fresh
+                            factor is never stored) and `out` must be NULL.  Same values as kfac_ema on a stored factor. */
+    float decay;
+    int32_t packed;      /* 1: `out` receives the packed upper triangle, d (d + 1) / 2 floats in the layout of
+                            kfac_pack_upper_batched (Sec. 3.4, symmetry-aware communication), instead of the square */
 } kfac_factor_item;
 
 int kfac_factor_batched(const kfac_factor_item* items_host, const kfac_factor_item* items_dev, int32_t count,

@@ -48,7 +48,8 @@ class kfac_layer_desc(ctypes.Structure):
 
 class kfac_factor_item(ctypes.Structure):
     _fields_ = [("desc", kfac_layer_desc), ("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p),
-                ("ws_bytes", ctypes.c_size_t), ("scale", ctypes.c_float), ("op", ctypes.c_int32)]
+                ("ws_bytes", ctypes.c_size_t), ("scale", ctypes.c_float), ("op", ctypes.c_int32),
+                ("running", ctypes.c_void_p), ("decay", ctypes.c_float), ("packed", ctypes.c_int32)]
 
 
 class kfac_ema_item(ctypes.Structure):
@@ -254,18 +255,22 @@ def kfac_factor_G(desc: kfac_layer_desc, gout: torch.Tensor, scale: float, G: to
 class FactorBatch:
     """Host + device copies of a kfac_factor_item table (built once, reused every step).
 
-    builds: sequence of (op, desc, x tensor, out tensor, scale)."""
+    builds: sequence of (op, desc, x tensor, out tensor, scale).
+    running: None, or one tensor per build: the build's result is folded into it (running average with `decay`) and the
+    out tensor of that build is not written.  packed: the out tensors receive packed upper triangles."""
 
-    def __init__(self, builds, device="cuda"):
+    def __init__(self, builds, device="cuda", running=None, decay: float = 0.0, packed: bool = False):
         n = len(builds)
         self.count = n
         self.ws = [alloc_workspace(kfac_factor_workspace_bytes(op, desc), device) for op, desc, _, _, _ in builds]
-        self.keep = list(builds)
+        self.keep = (list(builds), running)
         arr = (kfac_factor_item * n)()
         for i, (op, desc, x, out, scale) in enumerate(builds):
             ws = self.ws[i]
-            arr[i] = kfac_factor_item(desc, x.data_ptr(), out.data_ptr(), _ptr(ws),
-                                      0 if ws is None else ws.numel(), float(scale), int(op))
+            run = None if running is None else running[i]
+            arr[i] = kfac_factor_item(desc, x.data_ptr(), None if run is not None else out.data_ptr(), _ptr(ws),
+                                      0 if ws is None else ws.numel(), float(scale), int(op),
+                                      _ptr(run), float(decay) if run is not None else 0.0, int(bool(packed)))
         self.host = arr
         self.dev = torch.frombuffer(bytearray(bytes(arr)), dtype=torch.uint8).to(device)
 

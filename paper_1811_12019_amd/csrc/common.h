@@ -68,6 +68,38 @@ __device__ __forceinline__ KFAC_AS1 T* as_global(T* p) {
     return (KFAC_AS1 T*)p;
 }
 
+// Where a symmetric d x d result goes (the factor builders' epilogues):
+//   plain    dst = the d x d square, both triangles written
+//   ema      dst = the running average S, updated in place: S <- decay S + (1 - decay) value   (both triangles)
+//   packed   dst = the packed upper triangle (row r contributes columns r .. d-1), d (d + 1) / 2 floats
+struct OutSpec {
+    gfloat* dst;
+    float decay, one_minus;
+    int mode;                       // OUT_PLAIN, OUT_EMA, OUT_PACKED
+};
+constexpr int OUT_PLAIN = 0, OUT_EMA = 1, OUT_PACKED = 2;
+
+// first element of packed row r, minus r (so that adding a column index c >= r gives the element's place)
+__device__ __forceinline__ size_t packed_row_base(int r, int d) {
+    return (size_t)r * d - ((size_t)r * (r - 1)) / 2 - r;
+}
+
+// One element (row, col) of the result, row >= col or inside a diagonal tile that holds both triangles; `mirror`: the
+// element (col, row) is this call's to write too.  The slow, general form (the matrix-core epilogues have their own).
+__device__ __forceinline__ void emit_sym(const OutSpec& o, int d, int row, int col, float v, bool mirror) {
+    if (o.mode == OUT_PACKED) {
+        if (mirror || col >= row) {
+            const int r = min(row, col), c = max(row, col);
+            o.dst[packed_row_base(r, d) + c] = v;
+        }
+        return;
+    }
+    const size_t idx = (size_t)row * d + col;
+    if (o.mode == OUT_EMA) v = fmaf(o.decay, o.dst[idx], o.one_minus * v);
+    o.dst[idx] = v;
+    if (mirror) o.dst[(size_t)col * d + row] = v;
+}
+
 // lower-triangular tile index -> (I, J), I >= J, tiles numbered row by row
 __device__ __forceinline__ void tri_decode(int t, int& I, int& J) {
     int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);

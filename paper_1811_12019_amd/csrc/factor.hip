@@ -59,7 +59,7 @@ constexpr int GT = 64;   // generic kernel: output tile edge
 constexpr int GK = 16;   // unfolded rows per LDS stage
 
 __global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const void* __restrict__ x, float scale,
-                                                             float* __restrict__ out, float* __restrict__ partial,
+                                                             OutSpec os, float* __restrict__ partial,
                                                              int rows_per_split) {
     __shared__ float As[GK][GT + 4];
     __shared__ float Bs[GK][GT + 4];
@@ -152,11 +152,7 @@ __global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const voi
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int row = I * GT + ty * 4 + p, col = J * GT + tx * 4 + q;
-                if (row < u.d && col < u.d) {
-                    float v = acc[p][q] * scale;
-                    out[(size_t)row * u.d + col] = v;
-                    if (I != J) out[(size_t)col * u.d + row] = v;
-                }
+                if (row < u.d && col < u.d) emit_sym(os, u.d, row, col, acc[p][q] * scale, I != J);
             }
     } else {
         float* dst = partial + ((size_t)split * gridDim.x + blockIdx.x) * (GT * GT);
@@ -172,7 +168,7 @@ __global__ __launch_bounds__(256) void factor_generic_kernel(Unfold u, const voi
 // partial reads are 128-byte runs; the mirror goes through an LDS transpose.
 template <int T>
 __device__ __forceinline__ void factor_reduce_block(const gfloat* __restrict__ partial, int nsplit, int ntiles,
-                                                    int tile, int sub, int d, float scale, gfloat* __restrict__ out,
+                                                    int tile, int sub, int d, float scale, const OutSpec& os,
                                                     float (*tr)[33]) {
     int I, J;
     tri_decode(tile, I, J);
@@ -196,9 +192,30 @@ __device__ __forceinline__ void factor_reduce_block(const gfloat* __restrict__ p
         }
         for (; sp < nsplit; ++sp) s += *(const KFAC_AS1 v4f*)(src + (size_t)sp * stride);
         s *= scale;
+        gfloat* __restrict__ out = os.dst;
+        if (os.mode == OUT_PACKED) {                                 // only elements on or above the diagonal exist
+            if (I == J) {
+                const size_t rb = packed_row_base(row, d);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (col + q < d) out[(size_t)row * d + col + q] = s[q];
+                for (int q = 0; q < 4; ++q)
+                    if (col + q < d && col + q >= row) out[rb + col + q] = s[q];
+            }
+        } else {
+            if (os.mode == OUT_EMA) {
+                if (col + 3 < d) {
+                    const v4f o = *(const KFAC_AS1 v4f_a4*)(out + (size_t)row * d + col);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) s[q] = fmaf(os.decay, o[q], os.one_minus * s[q]);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (col + q < d) s[q] = fmaf(os.decay, out[(size_t)row * d + col + q], os.one_minus * s[q]);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (col + q < d) out[(size_t)row * d + col + q] = s[q];
+        }
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) tr[lr][lc + q] = s[q];
@@ -207,17 +224,18 @@ __device__ __forceinline__ void factor_reduce_block(const gfloat* __restrict__ p
     // transposed: thread (lr, lc..lc+3) now owns mirrored row (J*T + sj*32 + lr), columns I*T + si*32 + lc..+3
     const int mrow = J * T + sj * 32 + lr, mcol = I * T + si * 32 + lc;
     if (mrow < d) {
+        gfloat* __restrict__ mout = os.dst + (os.mode == OUT_PACKED ? packed_row_base(mrow, d) : (size_t)mrow * d);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            if (mcol + q < d) out[(size_t)mrow * d + mcol + q] = tr[lc + q][lr];
+            if (mcol + q < d) mout[mcol + q] = tr[lc + q][lr];
     }
 }
 
 template <int T>
 __global__ __launch_bounds__(256) void factor_reduce_kernel(const float* __restrict__ partial, int nsplit, int d,
-                                                            float scale, float* __restrict__ out) {
+                                                            float scale, OutSpec os) {
     __shared__ float tr[32][33];
-    factor_reduce_block<T>(as_global(partial), nsplit, gridDim.x, blockIdx.x, blockIdx.y, d, scale, as_global(out), tr);
+    factor_reduce_block<T>(as_global(partial), nsplit, gridDim.x, blockIdx.x, blockIdx.y, d, scale, os, tr);
 }
 
 struct FactorPlan {
@@ -295,6 +313,16 @@ static FactorPlan plan_gather(const Unfold& u) {
     return p;
 }
 
+// Where an item's result goes.
+static __host__ __device__ __forceinline__ OutSpec out_spec(const kfac_factor_item& it) {
+    OutSpec o;
+    o.decay = it.decay;
+    o.one_minus = 1.0f - it.decay;
+    if (it.running) { o.dst = (gfloat*)it.running; o.mode = OUT_EMA; }
+    else { o.dst = (gfloat*)it.out; o.mode = it.packed ? OUT_PACKED : OUT_PLAIN; }
+    return o;
+}
+
 // ---- batched launches: many factor builds in one grid -------------------------------------------------------------
 constexpr int FMAXB = 120;
 
@@ -327,7 +355,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) voi
     if (it.op == KFAC_OP_FACTOR_A) make_unfold_A(&it.desc, &u); else make_unfold_G(&it.desc, &u);
     const FactorPlan p = plan_dma(u, b.target);
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
-    factor_dma_tile<PLAIN, F16>(u, (const KFAC_AS1 unsigned char*)it.x, scale, as_global(it.out),
+    factor_dma_tile<PLAIN, F16>(u, (const KFAC_AS1 unsigned char*)it.x, scale, out_spec(it),
                                 as_global((float*)it.ws), p.rows_per_split, p.ntiles, p.nsplit, local, smem);
 }
 
@@ -342,7 +370,7 @@ __global__ __launch_bounds__(256) void factor_reduce_batched_kernel(FBatch b) {
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     constexpr int SUBS = (FT / 32) * (FT / 32);
     factor_reduce_block<FT>(as_global((const float*)it.ws), p.nsplit, p.ntiles, local / SUBS, local % SUBS, u.d, scale,
-                            as_global(it.out), tr);
+                            out_spec(it), tr);
 }
 
 static bool item_unfold(const kfac_factor_item& it, Unfold* u) {
@@ -362,7 +390,10 @@ static size_t item_ws_bytes(const Unfold& u) {
 
 static int check_item(const kfac_factor_item& it, Unfold* u) {
     if (!item_unfold(it, u)) return KFAC_ERR_INVALID_ARG;
-    if (!it.x || !it.out) return KFAC_ERR_INVALID_ARG;
+    if (!it.x) return KFAC_ERR_INVALID_ARG;
+    // exactly one destination: the fresh factor (square or packed) or the running average it is folded into
+    if (it.running ? (it.out != nullptr || it.packed != 0 || !(it.decay >= 0.f && it.decay <= 1.f)) : !it.out) return KFAC_ERR_INVALID_ARG;
+    if (it.packed != 0 && it.packed != 1) return KFAC_ERR_INVALID_ARG;
     const size_t need = item_ws_bytes(*u);
     if (need > 0 && (!it.ws || ((uintptr_t)it.ws & 255) || it.ws_bytes < need)) return KFAC_ERR_WORKSPACE;
     return KFAC_OK;
@@ -392,7 +423,7 @@ static int run_gather(const Unfold& u, const kfac_factor_item& it, hipStream_t s
         KFAC_LAUNCH(factor_gather_kernel<false>, dim3(p.nsplit), dim3(256), stream, u, it.x, (float*)it.ws, p.rows_per_split);
     }
     KFAC_LAUNCH(factor_gather_reduce_kernel, dim3(p.ntiles * GA_T), dim3(256), stream, (const float*)it.ws, p.nsplit, p.ntiles,
-                u.d, scale, it.out);
+                u.d, scale, out_spec(it));
     return KFAC_OK;
 }
 
@@ -401,10 +432,10 @@ static int run_generic(const Unfold& u, const kfac_factor_item& it, hipStream_t 
     const float scale = it.scale == 0.f ? 1.0f / (float)u.R : it.scale;
     FactorPlan p = plan_generic(u);
     dim3 grid(p.ntiles, p.nsplit);
-    KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, it.x, scale, it.out, (float*)it.ws, p.rows_per_split);
+    KFAC_LAUNCH(factor_generic_kernel, grid, dim3(256), stream, u, it.x, scale, out_spec(it), (float*)it.ws, p.rows_per_split);
     if (p.nsplit > 1) {
         KFAC_LAUNCH(factor_reduce_kernel<GT>, dim3(p.ntiles, (GT / 32) * (GT / 32)), dim3(256), stream,
-                    (const float*)it.ws, p.nsplit, u.d, scale, it.out);
+                    (const float*)it.ws, p.nsplit, u.d, scale, out_spec(it));
     }
     return KFAC_OK;
 }
@@ -489,6 +520,7 @@ static int factor_single(int op, const kfac_layer_desc* desc, const void* x, flo
     if (!desc) return KFAC_ERR_INVALID_ARG;
     kfac_factor_item it;
     it.desc = *desc; it.x = x; it.out = out; it.ws = ws; it.ws_bytes = ws_bytes; it.scale = scale; it.op = op;
+    it.running = nullptr; it.decay = 0.f; it.packed = 0;
     return run_factor_items(&it, nullptr, 1, (hipStream_t)stream);
 }
 

@@ -55,7 +55,7 @@ __device__ __forceinline__ v16f mfma16_halves(v2u a0, v2u a1, v2u b0, v2u b1, v1
 // One tile (workgroup `wg` of ntiles * nsplit) of one factor build.  x, out and partial are global-memory pointers.
 template <bool PLAIN, bool F16>
 __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 unsigned char* x, float scale,
-                                                gfloat* __restrict__ out, gfloat* __restrict__ partial,
+                                                const OutSpec os, gfloat* __restrict__ partial,
                                                 int rows_per_split, int ntiles, int nsplit, int wg,
                                                 unsigned char* smem) {
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
@@ -253,7 +253,15 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
                 }
         return;
     }
-    if (whole) {
+    gfloat* __restrict__ out = os.dst;
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) acc[p][q] *= scale;
+    if (os.mode == OUT_EMA) {
+        // running average folded in: the old values of this (lower) tile are read, all loads before the first use; the
+        // mirror image gets the same new values (the running average is symmetric)
+        float old[2][2][16];
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
@@ -261,9 +269,40 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
-                    out[(size_t)row * u.d + col] = acc[p][q][r] * scale;
+                    old[p][q][r] = (whole || (row < u.d && col < u.d)) ? out[(size_t)row * u.d + col] : 0.f;
                 }
-    } else {
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[p][q][r] = fmaf(os.decay, old[p][q][r], os.one_minus * acc[p][q][r]);
+    }
+    const bool packed = os.mode == OUT_PACKED;
+    if (!packed) {
+        if (whole) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
+                        out[(size_t)row * u.d + col] = acc[p][q][r];
+                    }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
+                        if (row < u.d && col < u.d) out[(size_t)row * u.d + col] = acc[p][q][r];
+                    }
+        }
+    } else if (diag) {
+        // packed upper triangle: of a diagonal tile, the elements on or above the diagonal, row by row
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
@@ -271,10 +310,11 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int row = i0 + p * 32 + (r >> 2) * 8 + h * 4 + (r & 3), col = j0 + q * 32 + lm;
-                    if (row < u.d && col < u.d) out[(size_t)row * u.d + col] = acc[p][q][r] * scale;
+                    if (row < u.d && col < u.d && col >= row) out[packed_row_base(row, u.d) + col] = acc[p][q][r];
                 }
     }
     if (diag) return;
+    // mirror image (rows of the upper triangle), transposed through LDS so that stores run along rows
     float* epi = (float*)smem + wave * (32 * FEPI_LD);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -283,9 +323,9 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = (r >> 2) * 8 + h * 4 + (r & 3), col = q * 32 + lm;
-                epi[row * FEPI_LD + col] = acc[p][q][r] * scale;
+                epi[row * FEPI_LD + col] = acc[p][q][r];
             }
-        if (whole) {
+        if (whole && !packed) {
 #pragma unroll 8
             for (int c2 = 0; c2 < 64; c2 += 2) {
                 const int c = c2 + h;
@@ -296,7 +336,7 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
                 int c = c2 + h;
                 int col = j0 + c, row = i0 + p * 32 + lm;
                 float v = epi[lm * FEPI_LD + c];
-                if (col < u.d && row < u.d) out[(size_t)col * u.d + row] = v;
+                if (col < u.d && row < u.d) out[(packed ? packed_row_base(col, u.d) : (size_t)col * u.d) + row] = v;
             }
         }
     }

@@ -123,10 +123,9 @@ __global__ __launch_bounds__(256) void factor_gather_kernel(Unfold u, const void
 // Sum of the partial factors: one workgroup per (block, row of the block).  32 lanes along the row times 8 groups
 // that each add every 8th partial, then a fixed-order sum of the 8 group totals: deterministic, 128-byte reads.
 __global__ __launch_bounds__(256) void factor_gather_reduce_kernel(const float* partial_, int nsplit, int ntiles, int d,
-                                                                   float scale, float* out_) {
+                                                                   float scale, OutSpec os) {
     __shared__ float part[8][32];
     const gfloat* __restrict__ partial = as_global(partial_);
-    gfloat* __restrict__ out = as_global(out_);
     const int tile = blockIdx.x >> 5, trow = blockIdx.x & 31;
     const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
     int I, J;
@@ -150,10 +149,7 @@ __global__ __launch_bounds__(256) void factor_gather_reduce_kernel(const float* 
         for (int g = 0; g < 8; ++g) s += part[g][col];
         s *= scale;
         const int row = I * GA_T + trow, c = J * GA_T + col;
-        if (row < d && c < d && (I != J || c <= row)) {
-            out[(size_t)row * d + c] = s;
-            out[(size_t)c * d + row] = s;
-        }
+        if (row < d && c < d && (I != J || c <= row)) emit_sym(os, d, row, c, s, row != c);
     }
 }
 

@@ -52,13 +52,17 @@ INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
 class _Wave:
     """A subset of the layers with batched-call tables of its own."""
 
-    def __init__(self, layers: List[LayerState], decay, damping: float, n_groups: int, device, pi_split: bool = False):
+    def __init__(self, layers: List[LayerState], decay, damping: float, n_groups: int, device, pi_split: bool = False,
+                 fused_ema: bool = False):
         self.layers = layers
         builds = []
         for l in layers:
             builds.append((kb.KFAC_OP_FACTOR_A, l.desc, l.act, l.A_new, 0.0))
             builds.append((kb.KFAC_OP_FACTOR_G, l.desc, l.gout, l.G_new, 0.0))
-        self.factor_batch = kb.FactorBatch(builds, device=device)
+        # fused: every build folds its result into the running average in its own epilogue (no fresh factor is stored)
+        self.fused_ema = bool(fused_ema and decay is not None)
+        self.factor_batch = (kb.FactorBatch(builds, device=device, running=[t for l in layers for t in (l.A_run, l.G_run)],
+                                            decay=decay) if self.fused_ema else kb.FactorBatch(builds, device=device))
         self.pre_batch = kb.PrecondBatch([l.G_inv for l in layers], [l.A_inv for l in layers],
                                          [l.gradW for l in layers], [l.P for l in layers], device=device)
         self.ema_batch = kb.EmaBatch([t for l in layers for t in (l.A_run, l.G_run)],
@@ -101,17 +105,18 @@ class KfacNetworkStep:
 
     def __init__(self, layers: Sequence[LayerShape], dtype: int = kb.KFAC_BF16, order: int = kb.KFAC_ORDER_KH_KW_C,
                  decay: Optional[float] = 0.95, gamma: float = 1e-3, seed: int = 0, device="cuda",
-                 inverse_streams: int = 3, long_dim: int = 2048, pi_split: bool = False):
+                 inverse_streams: int = 3, long_dim: int = 2048, pi_split: bool = False, fused_ema: bool = True):
         self.decay = decay
         self.gamma = float(gamma)
         self.pi_split = pi_split                     # False: sqrt(gamma) on each factor; True: the trace-ratio split
         self.damping = float(gamma) ** 0.5           # sqrt(gamma) on each factor
         self.layers: List[LayerState] = [LayerState(s, i, dtype, order, seed, device) for i, s in enumerate(layers)]
-        self.all = _Wave(self.layers, decay, self.damping, inverse_streams, device, pi_split)
+        self.fused_ema = bool(fused_ema and decay is not None)   # running averages formed by the builders themselves
+        self.all = _Wave(self.layers, decay, self.damping, inverse_streams, device, pi_split, fused_ema)
         long_ = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) >= long_dim]
         short = [l for l in self.layers if max(l.shape.d_A, l.shape.d_G) < long_dim]
-        self.waves = ([_Wave(long_, decay, self.damping, inverse_streams, device, pi_split),
-                       _Wave(short, decay, self.damping, 1, device, pi_split)] if long_ and short else [])
+        self.waves = ([_Wave(long_, decay, self.damping, inverse_streams, device, pi_split, fused_ema),
+                       _Wave(short, decay, self.damping, 1, device, pi_split, fused_ema)] if long_ and short else [])
         self.inv_streams = [torch.cuda.Stream(device=device) for _ in range(max(1, inverse_streams))]
         self.overlap_inversions = True      # False: run the groups one after the other on the caller's stream
         self.pipelined = True               # False: step() runs stage after stage
@@ -121,7 +126,7 @@ class KfacNetworkStep:
         kb.kfac_factor_batched(self.all.factor_batch, stream)
 
     def update_running(self, stream=None):
-        if self.decay is None:
+        if self.decay is None or self.fused_ema:
             return
         kb.kfac_ema_batched(self.all.ema_batch, self.decay, stream)
 
@@ -177,12 +182,12 @@ class KfacNetworkStep:
         main = torch.cuda.current_stream() if stream is None else stream
         lw, sw = self.waves
         kb.kfac_factor_batched(lw.factor_batch, main)
-        if self.decay is not None:
+        if self.decay is not None and not self.fused_ema:
             kb.kfac_ema_batched(lw.ema_batch, self.decay, main)
         self._split_damping(lw, main)
         joins = self._fork(lw.inv_batches, self.inv_streams, main)
         kb.kfac_factor_batched(sw.factor_batch, main)
-        if self.decay is not None:
+        if self.decay is not None and not self.fused_ema:
             kb.kfac_ema_batched(sw.ema_batch, self.decay, main)
         self._split_damping(sw, main)
         for batch in sw.inv_batches:

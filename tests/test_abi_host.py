@@ -36,7 +36,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(kb.kfac_layer_desc) == 13 * 4
     assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8 + 8
     assert ctypes.sizeof(kb.kfac_precond_item) == 5 * 8 + 8
-    assert ctypes.sizeof(kb.kfac_factor_item) == 56 + 4 * 8 + 8
+    assert ctypes.sizeof(kb.kfac_factor_item) == 56 + 4 * 8 + 8 + 16
 
 
 def test_workspace_sizes():
@@ -73,9 +73,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_factor_G(ctypes.byref(big), fake, 0.0, fake, ctypes.c_void_p(0x1010), 1 << 40, None) == kb.KFAC_ERR_WORKSPACE
 
     fit = (kb.kfac_factor_item * 1)()
-    fit[0] = kb.kfac_factor_item(big, 0x1000, 0x2000, None, 0, 0.0, kb.KFAC_OP_FACTOR_G)       # needs scratch, has none
+    fit[0] = kb.kfac_factor_item(big, 0x1000, 0x2000, None, 0, 0.0, kb.KFAC_OP_FACTOR_G, None, 0.0, 0)       # needs scratch, has none
     assert lib.kfac_factor_batched(fit, fake, 1, None) == kb.KFAC_ERR_WORKSPACE
-    fit[0] = kb.kfac_factor_item(big, 0x1000, 0x2000, None, 0, 0.0, 9)                          # unknown op
+    fit[0] = kb.kfac_factor_item(big, 0x1000, 0x2000, None, 0, 0.0, 9, None, 0.0, 0)                          # unknown op
     assert lib.kfac_factor_batched(fit, fake, 1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_factor_batched(fit, None, 1, None) == kb.KFAC_ERR_INVALID_ARG
 

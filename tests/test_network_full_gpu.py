@@ -18,8 +18,13 @@ from paper_1811_12019_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-FACTOR_TOL = 2e-5       # relative Frobenius; fp32 accumulation of exact bf16 products (the stated bar is 1e-2)
-FACTOR_MAX_TOL = 1e-5   # element-wise, relative to the largest entry of the factor
+# The fresh factor is not stored in this schedule; the one implied by the running average, (S - rho I) / (1 - rho), carries
+# the fp32 rounding of S (half an ulp of ~1, 3e-8) divided by 1 - rho = 0.05 and by the factor's own size (1e-2 for the G
+# factors): up to 1e-4 of its largest entry.  The stated bar is 1e-2; the builders alone are held to 2e-5 in
+# test_parity_gpu.py, on the same full-size layers.
+FACTOR_TOL = 5e-4
+FACTOR_MAX_TOL = 5e-4
+EMA_TOL = 1e-6          # relative Frobenius, running average (mostly the identity it started from)
 EMA_MAX_TOL = 2e-7      # element-wise, relative to the largest entry (one fp32 multiply-add per element)
 INV_TOL = 1e-4          # relative Frobenius (the stated bar)
 INV_MAX_TOL = 1e-4      # element-wise, relative to the largest entry of the inverse
@@ -51,10 +56,10 @@ def net():
     from paper_1811_12019_amd import step as kstep
     n = kstep.KfacNetworkStep(LAYERS, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=DECAY, gamma=GAMMA,
                               seed=0, device="cuda")
-    assert n.pipelined and len(n.waves) == 2                         # the schedule the benchmark times
+    assert n.pipelined and len(n.waves) == 2 and n.fused_ema         # the schedule the benchmark times
     assert max(b.count for w in n.waves for b in w.inv_batches) > 64  # more matrices than one launch group holds
     for l in n.layers:                                                # poison every output: nothing may be left unwritten
-        for t in (l.A_new, l.G_new, l.A_inv, l.G_inv, l.P):
+        for t in (l.A_inv, l.G_inv, l.P):
             t.fill_(float("nan"))
     n.step()
     torch.cuda.synchronize()
@@ -77,26 +82,26 @@ def test_resnet50_batch32_step_layer(net, idx):
     l = net.layers[idx]
     s = l.shape
     lam = float(np.float32(ko.factor_damping(GAMMA)))
-    A_new, G_new = f64(l.A_new), f64(l.G_new)
     A_run, G_run = f64(l.A_run), f64(l.G_run)
     A_inv, G_inv = f64(l.A_inv), f64(l.G_inv)
     P = f64(l.P)
-    for m in (A_new, G_new, A_run, G_run, A_inv, G_inv, P):
+    for m in (A_run, G_run, A_inv, G_inv, P):
         assert np.isfinite(m).all(), s.name
-    # stages 1, 2: factors from the bf16 tensors the GPU read
-    for tag, got, ref in (("A", A_new, ko.factor_A(nchw(l.act), s.kh, s.kw, s.stride, s.pad, True, ko.ORDER_KH_KW_C)),
-                          ("G", G_new, ko.factor_G(nchw(l.gout)))):
-        fro, mx = rel_fro(got, ref), rel_max(got, ref)
+    # stages 1, 2 and the running average from identity, formed in the builders' epilogues (the fresh factor is never
+    # stored): against the oracle's factor of the bf16 tensors the GPU read, folded into I by the oracle.  The fresh
+    # factor implied by the result, (S - rho I) / (1 - rho), meets the factor tolerance too.
+    for tag, got, ref in (("A", A_run, ko.factor_A(nchw(l.act), s.kh, s.kw, s.stride, s.pad, True, ko.ORDER_KH_KW_C)),
+                          ("G", G_run, ko.factor_G(nchw(l.gout)))):
+        want = ko.ema(np.eye(ref.shape[0]), ref, DECAY)
+        fro, mx = rel_fro(got, want), rel_max(got, want)
+        note("ema_" + tag, s.name, fro, mx)
+        assert fro < EMA_TOL and mx < EMA_MAX_TOL, (s.name, tag, fro, mx)
+        np.testing.assert_array_equal(got, got.T)
+        implied = (got - DECAY * np.eye(ref.shape[0])) / (1.0 - DECAY)
+        fro, mx = rel_fro(implied, ref), rel_max(implied, ref)
         note("factor_" + tag, s.name, fro, mx)
         assert fro < FACTOR_TOL and mx < FACTOR_MAX_TOL, (s.name, tag, fro, mx)
-        np.testing.assert_array_equal(got, got.T)
-    assert A_new[-1, -1] == pytest.approx(1.0, rel=1e-6)
-    # running average from identity, from the GPU's own fresh factor
-    for tag, got, fresh in (("A", A_run, A_new), ("G", G_run, G_new)):
-        ref = ko.ema(np.eye(fresh.shape[0]), fresh, DECAY)
-        mx = rel_max(got, ref)
-        note("ema_" + tag, s.name, rel_fro(got, ref), mx)
-        assert mx < EMA_MAX_TOL, (s.name, tag, mx)
+    assert A_run[-1, -1] == pytest.approx(1.0, rel=1e-6)
     # stage 4: damped inverse of the GPU's own running average
     for tag, got, run in (("A", A_inv, A_run), ("G", G_inv, G_run)):
         ref = ko.damped_inverse(run, lam)

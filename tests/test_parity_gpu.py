@@ -218,6 +218,74 @@ def test_factors_config2_full_size():
     assert A.shape == (148, 148) and G.shape == (64, 64)
 
 
+def _fused_and_packed_case(shapes, dtype=None):
+    dtype = kb.KFAC_BF16 if dtype is None else dtype
+    layout = kb.KFAC_NHWC if dtype != kb.KFAC_F32 else kb.KFAC_NCHW
+    rnd = _NP_ROUND[dtype]
+    builds, refs = [], []
+    for i, shp in enumerate(shapes):
+        desc = kb.make_desc(shp, layout, dtype, kb.KFAC_ORDER_KH_KW_C)
+        act, gout = rnd(synth.make_act(shp, 5, i)), rnd(synth.make_gout(shp, 5, i))
+        builds.append((kb.KFAC_OP_FACTOR_A, desc, kb.to_device_tensor(act, layout, dtype, DEV), shp.d_A))
+        refs.append(ko.factor_A(act, shp.kh, shp.kw, shp.stride, shp.pad, True, ko.ORDER_KH_KW_C))
+        builds.append((kb.KFAC_OP_FACTOR_G, desc, kb.to_device_tensor(gout, layout, dtype, DEV), shp.d_G))
+        refs.append(ko.factor_G(gout))
+    return builds, refs
+
+
+FUSED_SHAPES = [
+    synth.LayerShape("f.3x3", 3, 40, 9, 9, 70, 3, 3, 1, 1),                 # several tiles, ragged edges, one row split
+    synth.LayerShape("f.1x1long", 4, 64, 40, 40, 136, 1, 1, 1, 0),          # 6,400 rows: split over workgroups, reduced
+    synth.LayerShape("f.conv1", 2, 3, 70, 70, 16, 7, 7, 2, 3, relu_input=False),   # 3 channels: the narrow-layer kernel
+    synth.LayerShape("f.wide", 2, 160, 5, 5, 300, 3, 3, 1, 1),              # d_A = 1441: many whole tiles
+]
+
+
+def test_factor_batched_running_average_in_the_epilogue():
+    """Builds that fold their result into the running average themselves (Sec. 3.4 saves the traffic of a stored fresh
+    factor; the running average is this build's reading 5): S <- rho S + (1 - rho) X against the oracle, element-wise,
+    and bit for bit against building X and calling kfac_ema."""
+    decay = 0.95
+    builds, refs = _fused_and_packed_case(FUSED_SHAPES)
+    rng = np.random.default_rng(9)
+    S0 = []
+    for op, desc, x, d in builds:
+        m = rng.standard_normal((d, d)).astype(np.float32)
+        S0.append((m + m.T) * np.float32(0.5))
+    run_fused = [torch.from_numpy(s).to(DEV) for s in S0]
+    run_plain = [torch.from_numpy(s).to(DEV) for s in S0]
+    fresh = [torch.full((d, d), float("nan"), dtype=torch.float32, device=DEV) for _, _, _, d in builds]
+    items = [(op, desc, x, f, 0.0) for (op, desc, x, d), f in zip(builds, fresh)]
+    kb.kfac_factor_batched(kb.FactorBatch(items, device=DEV, running=run_fused, decay=decay))
+    kb.kfac_factor_batched(kb.FactorBatch(items, device=DEV))
+    kb.kfac_ema_batched(kb.EmaBatch(run_plain, fresh), decay)
+    torch.cuda.synchronize()
+    for s0, ref, got, plain in zip(S0, refs, run_fused, run_plain):
+        want = ko.ema(s0, ref, decay)
+        g = got.cpu().numpy()
+        assert rel_max(g, want) < 1e-6, rel_max(g, want)
+        np.testing.assert_array_equal(g, g.T)
+        np.testing.assert_array_equal(g, plain.cpu().numpy())
+
+
+def test_factor_batched_packed_upper_triangle_output():
+    """Builds that deliver the packed upper triangle (Sec. 3.4, symmetry-aware communication): against the oracle's
+    packing of the oracle's factor, and bit for bit against packing the full build."""
+    builds, refs = _fused_and_packed_case(FUSED_SHAPES)
+    packed = [torch.full((kb.packed_elems(d),), float("nan"), dtype=torch.float32, device=DEV) for _, _, _, d in builds]
+    full = [torch.empty((d, d), dtype=torch.float32, device=DEV) for _, _, _, d in builds]
+    kb.kfac_factor_batched(kb.FactorBatch([(op, desc, x, p, 0.0) for (op, desc, x, d), p in zip(builds, packed)],
+                                          device=DEV, packed=True))
+    kb.kfac_factor_batched(kb.FactorBatch([(op, desc, x, f, 0.0) for (op, desc, x, d), f in zip(builds, full)], device=DEV))
+    torch.cuda.synchronize()
+    for ref, p, f in zip(refs, packed, full):
+        got = p.cpu().numpy()
+        want = ko.pack_upper(ref)
+        assert np.isfinite(got).all()
+        assert rel_fro(got, want) < FACTOR_TOL and rel_max(got, want) < FACTOR_TOL
+        np.testing.assert_array_equal(got, ko.pack_upper(f.cpu().numpy()).astype(np.float32))
+
+
 # ----------------------------------------------------------------------------------------------
 # running average
 # ----------------------------------------------------------------------------------------------
@@ -740,7 +808,7 @@ def test_network_step_with_stale_inverses(long_dim):
     decay, gamma = 0.95, 1e-3
     lam = ko.factor_damping(gamma)
     net = kstep.KfacNetworkStep(NET_LAYERS, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=decay, gamma=gamma,
-                                seed=3, device=DEV, inverse_streams=2, long_dim=long_dim)
+                                seed=3, device=DEV, inverse_streams=2, long_dim=long_dim, fused_ema=False)
     assert len(net.waves) == (2 if long_dim == 140 else 0)
     f64 = lambda t: t.detach().cpu().numpy().astype(np.float64)
     nchw = lambda t: t.float().permute(0, 3, 1, 2).cpu().numpy().astype(np.float64)

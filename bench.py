@@ -6,6 +6,9 @@ already resident in HBM: 108 Kronecker-factor builds (bf16 inputs, fp32 accumula
 updates, 108 damped inverses (fp32) and 54 preconditioning products (fp32).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 32] [--no-cpu-baseline]
+  python bench.py --config cfg4     batch 128, gamma 1e-4, 20 steps, inverses refreshed at steps 0 and 10: amortised ms
+  python bench.py --only-steps      warm-up and timed steps only (one launch shape per kernel: for counter runs)
+  python bench.py --peaks           the machine's matrix-core and streaming peaks as the library's probes measure them
 
 One GPU only: the per-GPU share of the paper's data-parallel step is what is measured; --gpus N>1 exits.
 """
@@ -32,8 +35,7 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 157.3, "hbm": 8000.0}
 # split into three bf16 pieces (the sweep's panel product), 3 with both split two ways (two bf16 pieces:
 # preconditioning; two fp16 pieces of scaled operands: the sweep's rank-128 updates); fp16 and bf16 MFMA peaks are equal
 PEAK["mfma_bf16x3"] = round(PEAK["mfma_bf16"] / 6, 1)
-PEAK["mfma_bf16x2"] = round(PEAK["mfma_bf16"] / 3, 1)
-PEAK["mfma_f16x2"] = PEAK["mfma_bf16x2"]
+PEAK["mfma_f16x2"] = round(PEAK["mfma_bf16"] / 3, 1)
 
 
 def kernel_work(net: kstep.KfacNetworkStep):
@@ -58,13 +60,14 @@ def kernel_work(net: kstep.KfacNetworkStep):
         # flops (fp32 matrix cores), panel products of 2 d nb^2 (bf16 matrix cores, operands split three ways)
         "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_first_pivot_flops(d) for d in dims)),
         "inv_panel_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
-        "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
+        "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),
         "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),
         "factor_dma_kernel<plain>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_plain),
         "kfac::ema_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
         "kfac::ema_batched_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(12.0 * d * d for d in dims)),
+        "inv_init_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(4.0 * d * (d + 1) for d in dims if d > kstep.INVERSE_BLOCK)),
     }
     return w
 
@@ -157,37 +160,107 @@ def packed_triangle_rates(net, reps=5):
     return res
 
 
-def cpu_oracle_baseline(net, sample_names):
-    """The float64 oracle, as it stands, on a few layers of the same workload; scaled to a whole step by
-    algorithmic flops.  Reported baseline only."""
+def cpu_oracle_baseline(net):
+    """The float64 oracle, as it stands, on the whole step once: all 54 layers, same inputs (copied back from the
+    device), identity running averages.  Reported baseline only."""
     from oracle import kfac_oracle as ko
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-
-    def layer_flops(s):
-        return (kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) + kstep.inverse_flops(s.d_A) +
-                kstep.inverse_flops(s.d_G) + kstep.precondition_flops(s.d_G, s.d_A))
-
-    total = sum(layer_flops(l.shape) for l in net.layers)
-    sample = [l for l in net.layers if l.shape.name in sample_names]
-    sample_flops = sum(layer_flops(l.shape) for l in sample)
     t_cpu = 0.0
-    for l in sample:
+    for l in net.layers:
         s = l.shape
         act = l.act.float().permute(0, 3, 1, 2).cpu().numpy()
         gout = l.gout.float().permute(0, 3, 1, 2).cpu().numpy()
         gw = l.gradW.cpu().numpy()
         t0 = time.perf_counter()
         ko.kfac_layer_step(act, gout, gw, np.eye(s.d_A), np.eye(s.d_G), kh=s.kh, kw=s.kw, stride=s.stride, pad=s.pad,
-                           order=ko.ORDER_KH_KW_C, decay=net.decay, gamma=net.damping ** 2)
+                           order=ko.ORDER_KH_KW_C, decay=net.decay, gamma=net.gamma)
         t_cpu += time.perf_counter() - t0
-    est_ms = t_cpu * 1e3 * total / sample_flops
-    return {"value": round(est_ms, 1), "unit": "ms/step", "cores": int(threads), "kind": "oracle",
-            "sample": f"float64 numpy oracle on layers {sorted(sample_names)} ({t_cpu:.1f} s measured, "
-                      f"{100 * sample_flops / total:.1f}% of the step's algorithmic flops), scaled to all 54 layers by flops"}
+    return {"value": round(t_cpu * 1e3, 1), "unit": "ms/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 numpy oracle, one whole step: all {len(net.layers)} layers of the same workload "
+                      f"({t_cpu:.1f} s; host copies of the inputs not timed)"}
+
+
+def peaks():
+    """Matrix-core and streaming peaks of this GPU as the library's probes measure them (HIP events)."""
+    out = torch.empty(2048 * 256, device="cuda")
+    res = {}
+
+    def timed(fn, reps=3):
+        fn()
+        best = 1e30
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+
+    iters = 20000
+    for name, dt, flops in (("mfma_f32_32x32x2", kb.KFAC_F32, 4096), ("mfma_bf16_32x32x16", kb.KFAC_BF16, 32768),
+                            ("mfma_f16_32x32x16", kb.KFAC_F16, 32768)):
+        best = 0.0
+        for wgs in (256, 512, 1024, 2048):
+            ms = timed(lambda: kb.kfac_probe_mfma(dt, wgs, iters, out))
+            best = max(best, wgs * 4.0 * iters * 4 * flops / ms / 1e9)
+        res[name + "_tflops"] = round(best, 1)
+    src = torch.ones(1 << 29, dtype=torch.float32, device="cuda")       # 2 GiB
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, device="cuda")
+    nbytes = src.numel() * 4
+    bc = br = 0.0
+    for wgs in (1024, 4096, 16384):
+        bc = max(bc, 2.0 * nbytes / timed(lambda: kb.kfac_probe_copy(src, dst, wgs)) / 1e6)
+        br = max(br, 1.0 * nbytes / timed(lambda: kb.kfac_probe_read(src, sink, wgs)) / 1e6)
+    res["copy_gbs_read_plus_write"] = round(bc, 1)
+    res["read_gbs"] = round(br, 1)
+    res["published"] = {"mfma_bf16_tflops": PEAK["mfma_bf16"], "mfma_f32_tflops": PEAK["mfma_f32"], "hbm_gbs": PEAK["hbm"]}
+    return res
+
+
+def run_cfg4(args):
+    """configs[4]: batch 128, factors rebuilt and gradients preconditioned every step, inverses refreshed every 10th."""
+    layers = synth.resnet50_layers(128)
+    net = kstep.KfacNetworkStep(layers, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=0.95, gamma=1e-4, seed=0)
+    for _ in range(max(1, args.warmup)):
+        net.step(refresh_inverse=True)
+    net.reset_running()
+    torch.cuda.synchronize()
+    steps, every = 20, 10
+    t0 = time.perf_counter()
+    for i in range(steps):
+        net.step(refresh_inverse=(i % every == 0))
+    torch.cuda.synchronize()
+    total_ms = (time.perf_counter() - t0) * 1e3
+
+    def avg(fn, reps):
+        fn(); torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+
+    fresh_ms = avg(lambda: net.step(refresh_inverse=True), 3)
+    stale_ms = avg(lambda: net.step(refresh_inverse=False), 5)
+    assert int(net.inverse_info().abs().max()) == 0
+    fac_flops = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in layers)
+    print(json.dumps({
+        "metric": "ResNet-50 K-FAC step ms/GPU @ batch 128, inverses every 10th step (amortised over 20 steps)",
+        "value": round(total_ms / steps, 3), "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(total_ms / steps, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": DTYPE, "data": "synthetic",
+        "config": {"workload": "resnet50_kfac_step_all54layers_batch128_inverse_every10", "per_gpu_batch": 128,
+                   "layers": len(layers), "decay": 0.95, "gamma": 1e-4, "refresh_steps": [0, 10]},
+        "step_with_refresh_ms": round(fresh_ms, 3), "stale_step_ms": round(stale_ms, 3),
+        "factor_tflops_stale_step_bound": round(fac_flops / (stale_ms * 1e-3) / 1e12, 1)}))
+
+
+# what each stage computes in (the whole path stores and accumulates in fp32)
+DTYPE = ("bf16 factor inputs (exact products, f32 accumulate); f32 storage; inverse products on 16-bit matrix cores from "
+         "f32 operands split into 3 bf16 (panel) / 2 scaled f16 (rank-128 updates) pieces; preconditioning from 3 bf16 pieces")
 
 
 def main():
@@ -197,6 +270,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--config", default="cfg3", choices=["cfg3", "cfg4"])
+    ap.add_argument("--only-steps", action="store_true")
+    ap.add_argument("--peaks", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch three plain 1 GiB -> 1 GiB element-wise copies (torch.neg), for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by a kernel of known traffic")
@@ -209,12 +285,22 @@ def main():
         print("bench.py needs a GPU (no CPU fallback exists).", file=sys.stderr)
         sys.exit(3)
     kb.load_library()
+    if args.peaks:
+        print(json.dumps({"peaks": peaks()}))
+        return
+    if args.config == "cfg4":
+        run_cfg4(args)
+        return
 
     layers = synth.resnet50_layers(args.batch)
     net = kstep.KfacNetworkStep(layers, dtype=kb.KFAC_BF16, order=kb.KFAC_ORDER_KH_KW_C, decay=0.95, gamma=1e-3, seed=0)
     for _ in range(args.warmup):
         net.step()
     ms = timed_steps(net, args.steps)
+    if args.only_steps:
+        print(json.dumps({"value": round(ms, 3), "unit": "ms", "steps": args.steps, "warmup": args.warmup,
+                          "config": {"workload": f"resnet50_kfac_step_all54layers_batch{args.batch}"}}))
+        return
 
     stages = stage_times(net)
     # per-kernel durations over `steps` more steps, HIP events around every launch on the launch stream
@@ -263,7 +349,7 @@ def main():
         "metric": "ResNet-50 K-FAC step ms/GPU @ batch 32; factor TFLOP/s & % MFMA peak",
         "value": round(ms, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 factor inputs, f32 accumulate/inverse/precondition", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"resnet50_kfac_step_all54layers_batch{args.batch}", "per_gpu_batch": args.batch,
                    "layers": len(layers), "decay": 0.95, "gamma": 1e-3, "inverse_every_step": True},
         # stages run one after the other for the whole network; the timed step() overlaps them (the long inversion
@@ -277,9 +363,7 @@ def main():
     }
     out["next_rows"] = packed_triangle_rates(net)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_oracle_baseline(
-            net, {"conv1", "layer1.0.conv2", "layer2.1.conv1", "layer3.1.conv2", "layer3.2.conv2", "layer4.0.conv2",
-                  "layer4.1.conv2", "layer4.2.conv2", "layer4.0.downsample", "fc"})
+        out["cpu_baseline"] = cpu_oracle_baseline(net)
     print(json.dumps(out))
 
 

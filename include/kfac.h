@@ -304,6 +304,16 @@ int kfac_precondition_batched(const kfac_precond_item* items_host, const kfac_pr
 int kfac_kernel_timing_enable(int enable);
 int kfac_kernel_timing_report(char* buf_host, size_t buf_bytes);
 
+/* Probes of what this GPU can at best deliver, for the rooflines (measurement aids too; the caller times them).
+ * kfac_probe_mfma: `workgroups` x 4 wavefronts each issue 4 * iters matrix-core instructions on register-resident
+ * operands: v_mfma_f32_32x32x2_f32 (dtype KFAC_F32: 4096 flops each), v_mfma_f32_32x32x16_bf16 / _f16 (KFAC_BF16 /
+ * KFAC_F16: 32768 flops each).  out: workgroups * 256 device floats.
+ * kfac_probe_copy / kfac_probe_read: a plain streaming copy src -> dst, or read of src, of `bytes` bytes (a multiple
+ * of 16, 16-byte aligned buffers) by `workgroups` workgroups; sink: one device float. */
+int kfac_probe_mfma(int32_t dtype, int32_t workgroups, int32_t iters, float* out, void* stream);
+int kfac_probe_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream);
+int kfac_probe_read(const void* src, float* sink, size_t bytes, int32_t workgroups, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

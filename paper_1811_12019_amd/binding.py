@@ -37,7 +37,7 @@ EXPORTED_SYMBOLS = (
     "kfac_pi_damping_batched", "kfac_warmup_damping_alpha", "kfac_warmup_damping_next", "kfac_bn_damping",
     "kfac_refresh_interval",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
-    "kfac_kernel_timing_enable", "kfac_kernel_timing_report",
+    "kfac_kernel_timing_enable", "kfac_kernel_timing_report", "kfac_probe_mfma", "kfac_probe_copy", "kfac_probe_read",
 )
 
 
@@ -181,6 +181,12 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_kernel_timing_enable.argtypes = [ctypes.c_int]
     lib.kfac_kernel_timing_report.restype = ctypes.c_int
     lib.kfac_kernel_timing_report.argtypes = [ctypes.c_char_p, sz]
+    lib.kfac_probe_mfma.restype = ctypes.c_int
+    lib.kfac_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
+    lib.kfac_probe_copy.restype = ctypes.c_int
+    lib.kfac_probe_copy.argtypes = [vp, vp, sz, i32, vp]
+    lib.kfac_probe_read.restype = ctypes.c_int
+    lib.kfac_probe_read.argtypes = [vp, vp, sz, i32, vp]
     _lib = lib
     return lib
 
@@ -571,6 +577,20 @@ def kfac_precondition_batched(batch: PrecondBatch, stream=None) -> None:
 
 def kfac_kernel_timing_enable(enable: bool) -> None:
     _check(load_library().kfac_kernel_timing_enable(int(bool(enable))), "kfac_kernel_timing_enable")
+
+
+def kfac_probe_mfma(dtype: int, workgroups: int, iters: int, out: torch.Tensor, stream=None) -> None:
+    _check(load_library().kfac_probe_mfma(int(dtype), int(workgroups), int(iters), _ptr(out), _stream(stream)), "kfac_probe_mfma")
+
+
+def kfac_probe_copy(src: torch.Tensor, dst: torch.Tensor, workgroups: int, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().kfac_probe_copy(_ptr(src), _ptr(dst), nbytes, int(workgroups), _stream(stream)), "kfac_probe_copy")
+
+
+def kfac_probe_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().kfac_probe_read(_ptr(src), _ptr(sink), nbytes, int(workgroups), _stream(stream)), "kfac_probe_read")
 
 
 def kfac_kernel_timing_report() -> dict:

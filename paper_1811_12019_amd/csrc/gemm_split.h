@@ -8,14 +8,14 @@
 // v_mfma_f32_32x32x16_bf16 runs at 16 times the rate of v_mfma_f32_32x32x2_f32, so 3 (6) products per fp32
 // product still leave a factor 5.3 (2.7) over the fp32 matrix-core peak.
 //
-// (A variant with two fp16 pieces of scaled operands, three products, is at the end of this file.)
+// (A variant with two fp16 pieces of scaled operands, split ahead of time by the producer, is at the end of this file.)
 //
 // One workgroup = 4 wavefronts in a 2 x 2 arrangement, each owning a 64 x 64 quadrant as 2 x 2 MFMA blocks.  K
 // advances 16 at a time through a double-buffered LDS stage: the next slab is fetched into registers while the
 // current one is multiplied, then split and stored to the other buffer; one barrier per slab.
 // LDS layout per buffer: operand (A, B) x piece x 128 rows x 32 bytes (16 bf16 = the slab's K); the two 16-byte
-// halves of a row are swapped on every other group of 4 rows, which makes the 16-byte MFMA operand reads
-// (32 consecutive rows per half-wave) bank-conflict free.
+// halves of a row swap places from one group of 4 rows to the next and again from one group of 8 to the next, which
+// makes the 16-byte MFMA operand reads (served 16 consecutive rows at a time from 64 banks) bank-conflict free.
 #pragma once
 
 #include "factor_mfma.h"
@@ -76,15 +76,15 @@ __device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, 
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const int row = lr + 64 * p;
-        w_off[p] = (unsigned)(row * 32 + (((kq >> 1) ^ ((row >> 2) & 1)) * 16) + (kq & 1) * 8);
+        w_off[p] = (unsigned)(row * 32 + (((kq >> 1) ^ ((row >> 2) & 1) ^ ((row >> 3) & 1)) * 16) + (kq & 1) * 8);
     }
     // consumer: byte offsets (inside one piece plane) of this lane's 16 bytes for row blocks 0, 1
     unsigned a_off[2], b_off[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const int ra = wm * 64 + q * 32 + lm, rb = wn * 64 + q * 32 + lm;
-        a_off[q] = (unsigned)(ra * 32 + ((h ^ ((ra >> 2) & 1)) * 16));
-        b_off[q] = (unsigned)(rb * 32 + ((h ^ ((rb >> 2) & 1)) * 16) + NS * SPLIT_PLANE);
+        a_off[q] = (unsigned)(ra * 32 + ((h ^ ((ra >> 2) & 1) ^ ((ra >> 3) & 1)) * 16));
+        b_off[q] = (unsigned)(rb * 32 + ((h ^ ((rb >> 2) & 1) ^ ((rb >> 3) & 1)) * 16) + NS * SPLIT_PLANE);
     }
 
     // Two register sets: the slab two stages ahead is in flight while the current one is multiplied, so a fetch
@@ -208,95 +208,6 @@ __device__ __forceinline__ float panel_scale(float amax) {
     return ldexpf(1.0f, -e);
 }
 
-// acc[128 x 128] -= (sa A)(sb B)^T for complete, 16-byte aligned panels of NST * 16 columns (see tile_mma_nt_split with
-// NST > 0): both operands fp32, scaled by sa / sb and split into two fp16 pieces on the fly.
-// pre: acc is multiplied by it first (the caller's scaling of what acc already holds), as late as possible: acc may
-// still be arriving from memory while the first slabs are fetched and split.
-// lds: split_lds_bytes<2>() bytes.  Every wavefront multiplies (no branches), also the quadrant a diagonal tile does
-// not need.
-template <int NST>
-__device__ __forceinline__ void tile_mms_nt_split_h2(const gfloat* __restrict__ A, int lda, float sa,
-                                                     const gfloat* __restrict__ B, int ldb, float sb,
-                                                     unsigned char* __restrict__ lds, TileAcc& acc, float pre) {
-    constexpr int NS = 2;
-    constexpr int BUF = 2 * NS * SPLIT_PLANE;          // bytes per buffer
-    const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int lm = lane & 31, h = lane >> 5;
-    const int lr = t >> 2, kq = t & 3;
-    unsigned w_off[2];
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int row = lr + 64 * p;
-        w_off[p] = (unsigned)(row * 32 + (((kq >> 1) ^ ((row >> 2) & 1)) * 16) + (kq & 1) * 8);
-    }
-    unsigned a_off[2], b_off[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int ra = wm * 64 + q * 32 + lm, rb = wn * 64 + q * 32 + lm;
-        a_off[q] = (unsigned)(ra * 32 + ((h ^ ((ra >> 2) & 1)) * 16));
-        b_off[q] = (unsigned)(rb * 32 + ((h ^ ((rb >> 2) & 1)) * 16) + NS * SPLIT_PLANE);
-    }
-    const float nsa = -sa;
-    v4f ra[2][2], rb[2][2];
-    auto fetch = [&](int k0, v4f (&xa)[2], v4f (&xb)[2]) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int row = lr + 64 * p;
-            xa[p] = *(const KFAC_AS1 v4f*)(A + (size_t)row * lda + k0 + 4 * kq);
-            xb[p] = *(const KFAC_AS1 v4f*)(B + (size_t)row * ldb + k0 + 4 * kq);
-        }
-    };
-    auto stash = [&](int buf, const v4f (&xa)[2], const v4f (&xb)[2]) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            uint2 pa[NS], pb[NS];
-            split4_h2(xa[p] * nsa, pa);                // scaled and negated here, not at the fetch
-            split4_h2(xb[p] * sb, pb);
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                *(uint2*)(lds + buf * BUF + s * SPLIT_PLANE + w_off[p]) = pa[s];
-                *(uint2*)(lds + buf * BUF + (NS + s) * SPLIT_PLANE + w_off[p]) = pb[s];
-            }
-        }
-    };
-    auto mma = [&](int buf) {
-        uint4 a[2][NS], b[2][NS];
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int p = 0; p < NS; ++p) {
-                a[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + a_off[q]);
-                b[q][p] = *(const uint4*)(lds + buf * BUF + p * SPLIT_PLANE + b_off[q]);
-            }
-        // smallest terms first
-#pragma unroll
-        for (int order = NS - 1; order >= 0; --order)
-#pragma unroll
-            for (int pa = 0; pa <= order; ++pa)
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-                        acc.c[mb][nb] = mfma16<true>(a[mb][pa], b[nb][order - pa], acc.c[mb][nb]);
-    };
-    fetch(0, ra[0], rb[0]);
-    if (NST > 1) fetch(SPLIT_KS, ra[1], rb[1]);
-    stash(0, ra[0], rb[0]);
-    __syncthreads();
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) acc.c[mb][nb] *= pre;
-#pragma unroll
-    for (int s = 0; s < NST; ++s) {
-        if (s + 2 < NST) fetch((s + 2) * SPLIT_KS, ra[s & 1], rb[s & 1]);
-        mma(s & 1);
-        if (s + 1 < NST) stash((s + 1) & 1, ra[(s + 1) & 1], rb[(s + 1) & 1]);
-        __syncthreads();
-    }
-}
-
 // ---- operands split ahead of time ----------------------------------------------------------------------------------
 // A panel (128-row slabs x 128 columns of the contraction index) that many tile products read is scaled and split
 // into its two fp16 pieces once, by the kernel that produces it, instead of by every product that consumes it: the
@@ -329,15 +240,18 @@ __device__ __forceinline__ void store_split4_h2(KFAC_AS1 unsigned char* hi, KFAC
     *(KFAC_AS1 v2u_t*)(lo + off) = v2u_t{piece[1].x, piece[1].y};
 }
 
-// The rank-128 products of a tile: product q reads the piece planes a_hi + q * stride (high pieces of the A slab), that
-// plus `plane` (low pieces), and likewise b_hi; scale[q] = sa * sb is what the product of the stored pieces is scaled by.
+// The rank-128 products of a tile.  The operands of consecutive products sit in consecutive buffers of a ring of `nbuf`
+// (a power of two) equally laid out buffers `stride` bytes apart: product q reads buffer (first + q) mod nbuf, the
+// high pieces of its A slab at a_hi + buffer * stride, the low pieces `plane` bytes further, and likewise b_hi;
+// scale[q] = sa * sb is what the product of the stored pieces is scaled by.
 template <int MAXN>
 struct SplitRun {
-    const KFAC_AS1 unsigned char* a_hi;
+    const KFAC_AS1 unsigned char* a_hi;                // in buffer 0
     const KFAC_AS1 unsigned char* b_hi;
     size_t plane;                                      // bytes from a high plane to its low plane
-    size_t stride;                                     // bytes from one product's planes to the next one's
+    size_t stride;                                     // bytes from one buffer to the next
     float scale[MAXN];
+    int first, nbuf;
     int n;                                             // 1 .. MAXN products
 };
 
@@ -365,8 +279,9 @@ __device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsi
     auto issue = [&](int s, int buf) {
         const int sc = s < nst ? s : nst - 1;          // past the end: re-read the last slice (never consumed)
         const int q = sc / NSL, ks = sc - q * NSL;
-        const KFAC_AS1 unsigned char* pa = p.a_hi + q * p.stride;
-        const KFAC_AS1 unsigned char* pb = p.b_hi + q * p.stride;
+        const size_t boff = (size_t)((p.first + q) & (p.nbuf - 1)) * p.stride;
+        const KFAC_AS1 unsigned char* pa = p.a_hi + boff;
+        const KFAC_AS1 unsigned char* pb = p.b_hi + boff;
         const KFAC_AS1 unsigned char* src[4] = {pa, pa + p.plane, pb, pb + p.plane};
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -375,15 +290,16 @@ __device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsi
                                              16, 0, 0);
     };
     float back = 1.0f;
-    issue(0, 0);
-    issue(1, 1);
+#pragma unroll
+    for (int s = 0; s < PRE_NS - 1; ++s) issue(s, s);
     for (int it = 0; it < nst; it += PRE_NS) {
 #pragma unroll
         for (int bi = 0; bi < PRE_NS; ++bi) {
             const int s = it + bi;
             if (s >= nst) break;                                            // uniform
+            static_assert(PRE_NS == 3, "the wait below counts (PRE_NS - 2) * 4 younger copies");
             asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");   // slice s landed (everybody's part)
-            issue(s + 2, (bi + 2) % PRE_NS);                                 // refill the slot slice s - 1 vacated
+            issue(s + PRE_NS - 1, (bi + PRE_NS - 1) % PRE_NS);               // refill the slot slice s - 1 vacated
             if (s % NSL == 0) {                                              // uniform: a new product begins
                 float sq = p.scale[0];
 #pragma unroll
@@ -400,8 +316,9 @@ __device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsi
             for (int q = 0; q < 2; ++q)
 #pragma unroll
                 for (int pc = 0; pc < 2; ++pc) {
-                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[q][pc]) : "v"(a_addr[q]), "n"(bi * PRE_STAGE + pc * PRE_BLOCK));
-                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[q][pc]) : "v"(b_addr[q]), "n"(bi * PRE_STAGE + pc * PRE_BLOCK));
+                    // (the stage's base goes into the address: an instruction offset holds 16 bits only)
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[q][pc]) : "v"(a_addr[q] + bi * PRE_STAGE), "n"(pc * PRE_BLOCK));
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[q][pc]) : "v"(b_addr[q] + bi * PRE_STAGE), "n"(pc * PRE_BLOCK));
                 }
             asm volatile("s_waitcnt lgkmcnt(0)"
                          : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]),

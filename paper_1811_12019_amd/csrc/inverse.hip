@@ -108,44 +108,45 @@ static inline __host__ __device__ Group group_of(int dim, int step) {
     if (g.m < 0 || g.j >= g.m) g.m = 0;
     return g;
 }
-// Tiles of the update launch of `step`, per matrix: "chain" tiles, which the following steps need at once, and "lag"
+// Tiles of the update launch of `step` = k, per matrix: "chain" tiles, which the next step needs at once, and "lag"
 // tiles.
-//   * Narrow launch (not the group's last step): chain = the tiles with an index among the blocks c still to come in
-//     the group (block row c: tiles (c, 0..c); block column c below the group: tiles (E.., c), E the first block after
-//     the group) and the diagonal tile (E, E), the first pivot block after the group; each sees this step only.
-//   * The group's last step: every other tile now owes the group's steps.  If a group of two or more steps follows,
-//     only the tiles that group needs at once are chain tiles (the same shape of list, for the next group's blocks;
-//     "urgent"); the rest of the matrix is dealt, as lag tiles, to that group's narrow launches, where it runs beside
-//     the pivot workgroups that set those launches' duration instead of prolonging this one.  Otherwise all tiles of
-//     the triangle are chain tiles (and in the matrix's last step, which writes the output).
+//   * Chain launch (every step but the two kinds below).  Inside a group, and from one group to the next, a tile is
+//     brought up to date only when the next step needs it:
+//       - the tiles of block column / row k + 1 (all of them but the diagonal one, which the look-ahead pivot workgroup
+//         takes): each sees, in one visit, every step it still owes, up to k -- at most the whole group before its own
+//         and its own group's steps so far (chain_tile);
+//       - the diagonal tiles of the blocks still to come in the group and of the first block after it, which are
+//         kept up to date step by step so that a look-ahead pivot never owes more than one product; in a group's last
+//         step these are the diagonal tiles of the next group's blocks and of the first block after those, which see
+//         the whole group.
+//     Every other tile owes the group's steps: the rest of the matrix is dealt, as lag tiles, to the next group's
+//     chain launches (all but its last), where it runs beside the pivot workgroups that set those launches' duration.
+//   * Whole: the last step of a group that is not followed by a group of two or more steps; all tiles of the triangle
+//     are brought up to date.
+//   * Last: the matrix's last step, which writes the output.
 // The panels of two consecutive groups coexist in the NBUF buffers, so lag tiles read the previous group's.
 struct Plan {
     Group g;
-    int kind;            // 0 narrow, 1 urgent, 2 whole triangle (group's last step), 3 whole triangle (matrix's last step)
-    int c_begin, c_end;  // kinds 0, 1: the list is built for blocks c_begin .. c_end - 1 (plus the diagonal tile c_end)
+    int kind;            // PLAN_CHAIN, PLAN_WHOLE, PLAN_LAST
+    int d_begin, d_end;  // chain: diagonal tiles of blocks d_begin .. d_end - 1
     int chain;           // number of chain tiles
     int lag;             // number of lag tiles in this launch
     int lag_off;         // index of the first one in the lag list
 };
-constexpr int PLAN_NARROW = 0, PLAN_URGENT = 1, PLAN_WHOLE = 2, PLAN_LAST = 3;
+constexpr int PLAN_CHAIN = 0, PLAN_WHOLE = 2, PLAN_LAST = 3;
 
-static inline __host__ __device__ int list_tiles(int n, int c_begin, int c_end) {
-    int t = 1;
-    for (int c = c_begin; c < c_end; ++c) t += c + 1 + n - c_end;
-    return t;
-}
 static inline __host__ __device__ Plan plan_of(int dim, int step) {
     const int n = nblk_of(dim);
     Plan p;
     p.g = group_of(dim, step);
     p.lag = p.lag_off = 0;
-    p.c_begin = p.c_end = 0;
+    p.d_begin = p.d_end = 0;
     if (p.g.m == 0) { p.kind = PLAN_LAST; p.chain = n * (n + 1) / 2; return p; }
     const int E = p.g.g0 + p.g.m;
     if (p.g.j < p.g.m - 1) {
-        p.kind = PLAN_NARROW;
-        p.c_begin = step + 1; p.c_end = E;
-        p.chain = list_tiles(n, p.c_begin, p.c_end);
+        p.kind = PLAN_CHAIN;
+        p.d_begin = step + 2; p.d_end = E + 1;
+        p.chain = n - 1 + p.d_end - p.d_begin;
         if (p.g.g0 > 0) {                                   // the previous group left its update of the bulk to this one
             const int nc = n - p.g.m;                       // (the tiles with no index inside this group)
             const int total = nc * (nc + 1) / 2, per = (total + p.g.m - 2) / (p.g.m - 1);
@@ -156,9 +157,9 @@ static inline __host__ __device__ Plan plan_of(int dim, int step) {
     }
     const Group next = group_of(dim, E);
     if (next.m >= 2) {
-        p.kind = PLAN_URGENT;
-        p.c_begin = E; p.c_end = E + next.m;
-        p.chain = list_tiles(n, p.c_begin, p.c_end);
+        p.kind = PLAN_CHAIN;
+        p.d_begin = E + 1; p.d_end = E + next.m + 1;
+        p.chain = n - 1 + p.d_end - p.d_begin;
     } else {
         p.kind = PLAN_WHOLE;
         p.chain = n * (n + 1) / 2;
@@ -169,23 +170,17 @@ static inline __host__ __device__ int update_tiles(int dim, int step) {
     const Plan p = plan_of(dim, step);
     return p.chain + p.lag;
 }
-// tile index of a narrow / urgent list -> (I, J)
-__device__ __forceinline__ void list_decode(int n, int c_begin, int c_end, int t, int& I, int& J) {
-    I = J = c_end;
-    for (int c = c_begin; c < c_end; ++c) {
-        const int cnt = c + 1 + n - c_end;
-        if (t < cnt) {
-            if (t <= c) { I = c; J = t; }
-            else { I = c_end + (t - c - 1); J = c; }
-            return;
-        }
-        t -= cnt;
-    }
+// Tile index of a chain list -> (I, J): block row c = step + 1 left of the diagonal, block column c below it, then
+// the diagonal tiles d_begin ..
+__device__ __forceinline__ void chain_decode(int n, int c, int d_begin, int t, int& I, int& J) {
+    if (t < c) { I = c; J = t; }
+    else if (t < n - 1) { I = t + 1; J = c; }
+    else { I = J = d_begin + (t - (n - 1)); }
 }
 // Index in the list of all lower tiles of an n x n tile triangle -> (I, J), in an order that keeps tiles sharing rows
 // and columns together: the triangle is cut into 8 x 8 super-blocks (row-major over the super-blocks, row-major inside
-// one).  A contiguous range of the list, which is what one XCD (one L2) gets, then reads about as many different T slabs
-// as U slabs, instead of a few T slabs and every U slab as in row-major order over the whole triangle.
+// one), so that a contiguous range of the list, which is what one XCD (one L2) gets, reads about as many different T
+// slabs as U slabs.
 constexpr int SB = 8;
 __device__ __forceinline__ void tri_decode_blocked(int n, int t, int& I, int& J) {
     int r0 = 0;
@@ -939,19 +934,23 @@ struct OldSrc {
 // and the result is stored from the registers: nothing is staged in LDS.
 // STORE = false: the new values stay in acc (valid where the tile has rows and columns;
 // the quadrant above the diagonal of a diagonal tile is not computed) and nothing is written.
-typedef SplitRun<GM> PanelRun;
+constexpr int MAXRUN = 2 * GM - 1;       // a tile can owe the whole group before and all but one step of its own group
+typedef SplitRun<MAXRUN> PanelRun;
 
-// The products of tile (I, J) with the panels of buffers first .. first + n - 1 (consecutive steps of one group).
-__device__ __forceinline__ PanelRun panel_run(const WsView& ws, int first, int n, int I, int J) {
+// The products of tile (I, J) with the panels of the n consecutive steps first_step .. first_step + n - 1 (buffer =
+// step mod NBUF).
+__device__ __forceinline__ PanelRun panel_run(const WsView& ws, int first_step, int n, int I, int J) {
     PanelRun r;
-    r.a_hi = ws.TH(first) + (size_t)I * PRE_SLAB;
-    r.b_hi = ws.UH(first) + (size_t)J * PRE_SLAB;
+    r.a_hi = ws.TH(0) + (size_t)I * PRE_SLAB;
+    r.b_hi = ws.UH(0) + (size_t)J * PRE_SLAB;
     r.plane = ws.plane;
     r.stride = ws.stride * sizeof(float);
+    r.first = first_step % NBUF;
+    r.nbuf = NBUF;
     r.n = n;
 #pragma unroll
-    for (int q = 0; q < GM; ++q) {
-        const int b = min(first + q, NBUF - 1);
+    for (int q = 0; q < MAXRUN; ++q) {
+        const int b = (first_step + q) % NBUF;
         r.scale[q] = ws.scaleT(b, I) * ws.scaleU(b, J);
     }
     return r;
@@ -1040,7 +1039,7 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     c.diag = true;
     TileAcc acc;
     const OldSrc o = {ws.W + (size_t)k0 * ws.ldw + k0, ws.ldw, 1};
-    const PanelRun pl = panel_run(ws, cur, 1, kn, kn);
+    const PanelRun pl = panel_run(ws, step, 1, kn, kn);
     upd_regular_mid_split<false>(c, o, pl, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
@@ -1144,7 +1143,40 @@ __device__ __forceinline__ void group_tile(const Item& it, const WsView& ws, int
         }
     }
     TileAcc acc;
-    const PanelRun run = panel_run(ws, gbuf + first, g.j - first + 1, I, J);
+    const PanelRun run = panel_run(ws, g.g0 + first, g.j - first + 1, I, J);
+    upd_regular_mid_split(c, o, run, (unsigned char*)lds, acc);
+}
+
+// Tile of block column / row c = k + 1 (not the diagonal one) in the chain launch of step k: brought up to date
+// through step k, whatever it owes.  With `other` its second index:
+//   other == k              it becomes part of panel k: T_I of this step (block column k)
+//   lo <= other < k         block column `other` was eliminated at a step inside the window the tile can owe: the tile
+//                           then became T_I of that step (not written to the working copy), and owes the steps after it
+//   otherwise               its value in the working copy is up to date through step lo - 1, lo the first step of the
+//                           group before c's own (the bulk update of that group ran while c's group had begun and
+//                           skipped the tiles with an index inside it), and it owes lo .. k.
+__device__ __forceinline__ void chain_tile(const Item& it, const WsView& ws, int I, int J, int k, float* __restrict__ lds) {
+    const int c1 = k + 1;
+    UpdCtx c;
+    c.W = ws.W; c.ldw = ws.ldw; c.T = ws.T(k % NBUF); c.out = it.Minv;
+    c.d = it.dim;
+    c.i0 = I * NB; c.j0 = J * NB;
+    c.irows = min(NB, c.d - c.i0); c.jrows = min(NB, c.d - c.j0);
+    c.nb = NB;
+    c.diag = false;
+    if (J == k) {                                        // (I == c1: the tile below the pivot block)
+        upd_panel<false>(c, true, lds);
+        return;
+    }
+    const int lo = max(0, c1 / GM * GM - GM);
+    OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
+    int first = lo;
+    if (I == c1 && J >= lo) {                            // (J < k here)
+        first = J + 1;
+        o = OldSrc{ws.T(J % NBUF) + (size_t)c.i0 * NB, NB, 1};
+    }
+    TileAcc acc;
+    const PanelRun run = panel_run(ws, first, k - first + 1, I, J);
     upd_regular_mid_split(c, o, run, (unsigned char*)lds, acc);
 }
 
@@ -1188,11 +1220,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
         group_tile(it, ws, I, J, pg, false, lds);
         return;
     }
-    if (pl.kind == PLAN_NARROW || pl.kind == PLAN_URGENT) list_decode(nblk, pl.c_begin, pl.c_end, tile, I, J);
-    else tri_decode_blocked(nblk, tile, I, J);
+    if (pl.kind == PLAN_CHAIN) {
+        chain_decode(nblk, step + 1, pl.d_begin, tile, I, J);
+        if (I != J) chain_tile(it, ws, I, J, step, lds);
+        else group_tile(it, ws, I, J, pl.g, pl.g.j < pl.g.m - 1, lds);   // kept up to date step by step inside a group
+        return;
+    }
+    tri_decode_blocked(nblk, tile, I, J);
     if (I == J && (I == step || I == step + 1)) return;  // this step's pivot block and the next one's are written elsewhere
-    if (pl.kind != PLAN_LAST) {
-        group_tile(it, ws, I, J, pl.g, pl.kind == PLAN_NARROW, lds);
+    if (pl.kind == PLAN_WHOLE) {
+        group_tile(it, ws, I, J, pl.g, false, lds);
         return;
     }
     const int cur = step % NBUF;

@@ -298,6 +298,12 @@ def main():
         net.step()
     ms = timed_steps(net, args.steps)
     if args.only_steps:
+        if args.calibrate_copy:
+            src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                torch.neg(src, out=dst)
+            torch.cuda.synchronize()
         print(json.dumps({"value": round(ms, 3), "unit": "ms", "steps": args.steps, "warmup": args.warmup,
                           "config": {"workload": f"resnet50_kfac_step_all54layers_batch{args.batch}"}}))
         return

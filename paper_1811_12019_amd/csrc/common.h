@@ -109,6 +109,32 @@ __device__ __forceinline__ void tri_decode(int t, int& I, int& J) {
     J = t - i * (i + 1) / 2;
 }
 
+// Index in the list of all lower tiles of an n x n tile triangle -> (I, J), in an order that keeps tiles sharing rows
+// and columns together: the triangle is cut into SB x SB super-blocks (row-major over the super-blocks, row-major
+// inside one), so that a contiguous range of the list, which is what one XCD (one L2) gets, reads about as many
+// different row panels as column panels instead of one or two of the former and all of the latter.
+template <int SB = 8>
+__device__ __forceinline__ void tri_decode_blocked(int n, int t, int& I, int& J) {
+    int r0 = 0;
+    for (;;) {                                           // super-row with rows r0 .. r0 + h - 1
+        const int h = min(SB, n - r0);
+        const int cnt = h * r0 + h * (h + 1) / 2;        // full super-blocks to the left, then the triangular one
+        if (t < cnt || r0 + SB >= n) break;
+        t -= cnt;
+        r0 += SB;
+    }
+    const int h = min(SB, n - r0);
+    if (t < h * r0) {
+        const int sj = t / (h * SB), in = t - sj * (h * SB);
+        I = r0 + in / SB;
+        J = sj * SB + in % SB;
+    } else {
+        tri_decode(t - h * r0, I, J);
+        I += r0;
+        J += r0;
+    }
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 __device__ __forceinline__ float half_bits_to_float(uint16_t b) {

@@ -171,7 +171,8 @@ __device__ __forceinline__ void factor_reduce_block(const gfloat* __restrict__ p
                                                     int tile, int sub, int d, float scale, const OutSpec& os,
                                                     float (*tr)[33]) {
     int I, J;
-    tri_decode(tile, I, J);
+    if constexpr (T == FT) tri_decode_blocked<4>(ceil_div(d, T), tile, I, J);   // (the matrix-core kernel's tile order)
+    else tri_decode(tile, I, J);
     constexpr int SB = T / 32;
     const int si = sub / SB, sj = sub - si * SB;
     const int lr = threadIdx.x >> 3, lc = (threadIdx.x & 7) * 4;

@@ -80,7 +80,7 @@ __device__ __forceinline__ void factor_dma_tile(const Unfold& u, const KFAC_AS1 
         tile = unit - split * ntiles;
     }
     int I, J;
-    tri_decode(tile, I, J);
+    tri_decode_blocked<4>(ceil_div(u.d, FT), tile, I, J);   // (tiles that share row panels run together: see the function)
     const bool diag = I == J;
     const int r_begin = split * rows_per_split;
     const int r_end = min(u.R, r_begin + rows_per_split);

@@ -177,31 +177,6 @@ __device__ __forceinline__ void chain_decode(int n, int c, int d_begin, int t, i
     else if (t < n - 1) { I = t + 1; J = c; }
     else { I = J = d_begin + (t - (n - 1)); }
 }
-// Index in the list of all lower tiles of an n x n tile triangle -> (I, J), in an order that keeps tiles sharing rows
-// and columns together: the triangle is cut into 8 x 8 super-blocks (row-major over the super-blocks, row-major inside
-// one), so that a contiguous range of the list, which is what one XCD (one L2) gets, reads about as many different T
-// slabs as U slabs.
-constexpr int SB = 8;
-__device__ __forceinline__ void tri_decode_blocked(int n, int t, int& I, int& J) {
-    int r0 = 0;
-    for (;;) {                                           // super-row with rows r0 .. r0 + h - 1
-        const int h = min(SB, n - r0);
-        const int cnt = h * r0 + h * (h + 1) / 2;        // full super-blocks to the left, then the triangular one
-        if (t < cnt || r0 + SB >= n) break;
-        t -= cnt;
-        r0 += SB;
-    }
-    const int h = min(SB, n - r0);
-    if (t < h * r0) {
-        const int sj = t / (h * SB), in = t - sj * (h * SB);
-        I = r0 + in / SB;
-        J = sj * SB + in % SB;
-    } else {
-        tri_decode(t - h * r0, I, J);
-        I += r0;
-        J += r0;
-    }
-}
 // index in the lag list of a group [E, E + m) -> (I, J): the lower triangle over the blocks outside the group
 __device__ __forceinline__ void lag_decode(int n, int E, int m, int t, int& I, int& J) {
     tri_decode_blocked(n - m, t, I, J);

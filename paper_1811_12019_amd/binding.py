@@ -263,12 +263,15 @@ class FactorBatch:
 
     builds: sequence of (op, desc, x tensor, out tensor, scale).
     running: None, or one tensor per build: the build's result is folded into it (running average with `decay`) and the
-    out tensor of that build is not written.  packed: the out tensors receive packed upper triangles."""
+    out tensor of that build is not written.  packed: the out tensors receive packed upper triangles.
+    ws: None (scratch is allocated here), or one scratch tensor (or None where none is needed) per build, at least
+    kfac_factor_workspace_bytes(op, desc) bytes each, which tables that never run at the same time may share."""
 
-    def __init__(self, builds, device="cuda", running=None, decay: float = 0.0, packed: bool = False):
+    def __init__(self, builds, device="cuda", running=None, decay: float = 0.0, packed: bool = False, ws=None):
         n = len(builds)
         self.count = n
-        self.ws = [alloc_workspace(kfac_factor_workspace_bytes(op, desc), device) for op, desc, _, _, _ in builds]
+        self.ws = (list(ws) if ws is not None else
+                   [alloc_workspace(kfac_factor_workspace_bytes(op, desc), device) for op, desc, _, _, _ in builds])
         self.keep = (list(builds), running)
         arr = (kfac_factor_item * n)()
         for i, (op, desc, x, out, scale) in enumerate(builds):
@@ -473,13 +476,15 @@ class InverseBatch:
 
     def __init__(self, S: Sequence[torch.Tensor], Minv: Sequence[torch.Tensor], dampings: Sequence[float],
                  info: Optional[torch.Tensor] = None, device="cuda",
-                 dampings_dev: Optional[Sequence[Optional[int]]] = None):
-        """dampings_dev[i]: None, or the device address of a float that replaces dampings[i] when the work runs."""
+                 dampings_dev: Optional[Sequence[Optional[int]]] = None, ws=None):
+        """dampings_dev[i]: None, or the device address of a float that replaces dampings[i] when the work runs.
+        ws: None (scratch is allocated here), or one scratch tensor per matrix of kfac_inverse_workspace_bytes(dim)
+        bytes, which tables that never run at the same time may share."""
         n = len(S)
         dims = [int(s.shape[0]) for s in S]
         self.order = sorted(range(n), key=lambda i: -dims[i])        # the ABI wants largest first
         self.count = n
-        self.ws = [alloc_workspace(kfac_inverse_workspace_bytes(d), device) for d in dims]
+        self.ws = list(ws) if ws is not None else [alloc_workspace(kfac_inverse_workspace_bytes(d), device) for d in dims]
         self.info = info if info is not None else torch.zeros(n, dtype=torch.int32, device=device)
         self.keep = (list(S), list(Minv))
         arr = (kfac_inverse_item * n)()
@@ -552,15 +557,17 @@ def kfac_precondition(Ginv: torch.Tensor, Ainv: torch.Tensor, gradW: torch.Tenso
 
 
 class PrecondBatch:
-    """Host + device copies of a kfac_precond_item table (built once, reused every step)."""
+    """Host + device copies of a kfac_precond_item table (built once, reused every step).  ws: None (scratch is
+    allocated here), or one scratch tensor per layer of kfac_precondition_workspace_bytes(d_G, d_A) bytes."""
 
     def __init__(self, Ginv: Sequence[torch.Tensor], Ainv: Sequence[torch.Tensor], gradW: Sequence[torch.Tensor],
-                 out: Sequence[torch.Tensor], device="cuda"):
+                 out: Sequence[torch.Tensor], device="cuda", ws=None):
         n = len(out)
         shapes = [tuple(g.shape) for g in gradW]
         self.order = sorted(range(n), key=lambda i: -shapes[i][1])       # large d_A first: best load balance
         self.count = n
-        self.ws = [alloc_workspace(kfac_precondition_workspace_bytes(dG, dA), device) for dG, dA in shapes]
+        self.ws = (list(ws) if ws is not None else
+                   [alloc_workspace(kfac_precondition_workspace_bytes(dG, dA), device) for dG, dA in shapes])
         self.keep = (list(Ginv), list(Ainv), list(gradW), list(out))
         arr = (kfac_precond_item * n)()
         for slot, i in enumerate(self.order):

@@ -44,6 +44,12 @@ class LayerState:
         self.A_run, self.G_run = torch.eye(dA, **f32), torch.eye(dG, **f32)      # running averages start at I
         self.A_inv, self.G_inv = torch.empty((dA, dA), **f32), torch.empty((dG, dG), **f32)
         self.P = torch.empty((dG, dA), **f32)
+        # scratch of the batched calls, owned here so that the call tables of the stage-wise schedule and of the two
+        # waves (which never run at the same time) share it
+        self.factor_ws = [kb.alloc_workspace(kb.kfac_factor_workspace_bytes(op, self.desc), device)
+                          for op in (kb.KFAC_OP_FACTOR_A, kb.KFAC_OP_FACTOR_G)]
+        self.inverse_ws = [kb.alloc_workspace(kb.kfac_inverse_workspace_bytes(d), device) for d in (dA, dG)]
+        self.pre_ws = kb.alloc_workspace(kb.kfac_precondition_workspace_bytes(dG, dA), device)
 
 
 INVERSE_BLOCK = 128     # elimination block of the library's blocked sweep
@@ -61,16 +67,20 @@ class _Wave:
             builds.append((kb.KFAC_OP_FACTOR_G, l.desc, l.gout, l.G_new, 0.0))
         # fused: every build folds its result into the running average in its own epilogue (no fresh factor is stored)
         self.fused_ema = bool(fused_ema and decay is not None)
+        fws = [w for l in layers for w in l.factor_ws]
         self.factor_batch = (kb.FactorBatch(builds, device=device, running=[t for l in layers for t in (l.A_run, l.G_run)],
-                                            decay=decay) if self.fused_ema else kb.FactorBatch(builds, device=device))
+                                            decay=decay, ws=fws) if self.fused_ema
+                             else kb.FactorBatch(builds, device=device, ws=fws))
         self.pre_batch = kb.PrecondBatch([l.G_inv for l in layers], [l.A_inv for l in layers],
-                                         [l.gradW for l in layers], [l.P for l in layers], device=device)
+                                         [l.gradW for l in layers], [l.P for l in layers], device=device,
+                                         ws=[l.pre_ws for l in layers])
         self.ema_batch = kb.EmaBatch([t for l in layers for t in (l.A_run, l.G_run)],
                                      [t for l in layers for t in (l.A_new, l.G_new)])
-        src, dst = [], []
+        src, dst, iws = [], [], []
         for l in layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
             dst += [l.A_inv, l.G_inv]
+            iws += l.inverse_ws
         # trace-ratio split of the damping between a layer's factors: computed on the device before the inversions,
         # which read their damping from there
         self.pi_batch = kb.PiBatch(src[0::2], src[1::2], device=device) if pi_split else None
@@ -87,7 +97,7 @@ class _Wave:
             groups[g].append(i)
             load[g] += float(src[i].shape[0]) ** 3
         self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [damping] * len(grp),
-                                            device=device,
+                                            device=device, ws=[iws[i] for i in grp],
                                             dampings_dev=None if lam_dev is None else [lam_dev[i] for i in grp])
                             for grp in groups if grp]
 

@@ -13,14 +13,18 @@
 // prefix table passed in the kernel arguments).
 //
 // Launch structure.  Pivot -> panel -> update -> next pivot is a chain of dependent launches, 37 links long for a
-// 4609-wide factor, so the launches are arranged to keep the chain short:
+// 4609-wide factor, so the launches are arranged to keep the chain short and the bulk of the flops off it:
 //   * the update launch of step k gives the tile that is pivot block k + 1 to a workgroup of its own, which updates
 //     it, keeps it in registers and inverts it at once: a step is two launches (panel, update), and the pivot runs
 //     beside the tile updates (inv_pivot_kernel only serves a matrix's first block and single-block matrices);
-//   * steps are taken in pairs while neither is the matrix's last: the first launch touches only what the second
-//     step's pivot and panel need, the second applies both rank-128 updates to every other tile in one pass.
-// Products: the panel on the bf16 matrix cores with operands split three ways, the updates on the fp16 matrix cores
-// with operands scaled per 128-row slab and split two ways (gemm_split.h); both to fp32 accuracy.
+//   * steps are taken in groups of GM; inside a group only the next panel's block column / row and the diagonal
+//     tiles of the blocks still to come are brought up to date, every other tile receives a whole group as one
+//     rank-(GM * 128) update during the next group's launches (see Plan below);
+//   * every matrix of a batch carries its own step number, so that matrices with fewer blocks spread their steps
+//     over the launches of the largest one.
+// Products: the panel on the bf16 matrix cores with operands split three ways; the updates on the fp16 matrix cores
+// from operands that the panel launch has already scaled per 128-row slab and split two ways, stored as planes that
+// go to LDS by DMA (gemm_split.h); both to fp32 accuracy.
 //
 // Storage.  The sweep works on a copy W of the matrix in the caller's workspace whose rows are padded to a
 // multiple of 32 floats, so that every 128-wide tile row is a run of whole 128-byte lines, and it keeps only the

@@ -208,6 +208,17 @@ __device__ __forceinline__ float panel_scale(float amax) {
     return ldexpf(1.0f, -e);
 }
 
+// Largest of the 256 threads' values (red: 4 floats of LDS); two barriers.  Must be called by all threads.
+__device__ __forceinline__ float block_absmax(float x, float* __restrict__ red) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    x = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    return x;
+}
+
 // ---- operands split ahead of time ----------------------------------------------------------------------------------
 // A panel (128-row slabs x 128 columns of the contraction index) that many tile products read is scaled and split
 // into its two fp16 pieces once, by the kernel that produces it, instead of by every product that consumes it: the
@@ -304,6 +315,102 @@ __device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsi
                 float sq = p.scale[0];
 #pragma unroll
                 for (int q = 1; q < MAXN; ++q) sq = s / NSL == q ? p.scale[q] : sq;
+                const float f = sq * back;
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) acc.c[mb][nb] *= f;
+                back = 1.0f / sq;
+            }
+            v4f a[2][2], b[2][2];                                            // (16 bytes = 8 fp16 each)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int pc = 0; pc < 2; ++pc) {
+                    // (the stage's base goes into the address: an instruction offset holds 16 bits only)
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[q][pc]) : "v"(a_addr[q] + bi * PRE_STAGE), "n"(pc * PRE_BLOCK));
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[q][pc]) : "v"(b_addr[q] + bi * PRE_STAGE), "n"(pc * PRE_BLOCK));
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]),
+                           "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]));
+            // smallest terms first
+#pragma unroll
+            for (int term = 0; term < 3; ++term)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                    {
+                        v8h av, bv;
+                        __builtin_memcpy(&av, &a[mb][term == 0 ? 1 : 0], 16);
+                        __builtin_memcpy(&bv, &b[nb][term == 1 ? 1 : 0], 16);
+                        acc.c[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc.c[mb][nb], 0, 0, 0);
+                    }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");            // ring idle: the LDS may be reused
+    return back;
+}
+
+// A long contraction: product q reads the q-th consecutive 128 x 128 block of its operands' planes (the blocks of one
+// 128-row slab of a matrix stored block by block along the contraction index); scale_lds[q] (LDS, filled and made
+// visible by the caller) is the product of the two blocks' scales.
+struct SplitSeq {
+    const KFAC_AS1 unsigned char* a_hi;                // first block of the A slab's high plane
+    const KFAC_AS1 unsigned char* b_hi;
+    size_t plane_a, plane_b;                           // bytes from each operand's high plane to its low plane
+    const float* scale_lds;
+    int n;
+    __device__ __forceinline__ const KFAC_AS1 unsigned char* a_blk(int q) const { return a_hi + (size_t)q * PRE_SLAB; }
+    __device__ __forceinline__ const KFAC_AS1 unsigned char* b_blk(int q) const { return b_hi + (size_t)q * PRE_SLAB; }
+    __device__ __forceinline__ size_t a_plane() const { return plane_a; }
+    __device__ __forceinline__ size_t b_plane() const { return plane_b; }
+    __device__ __forceinline__ float scale_of(int q) const { return scale_lds[q]; }
+};
+
+// The same product loop for a long contraction given as a SplitSeq (kept apart from the SplitRun form, whose register
+// allocation inside the sweep's update kernel is tight).
+__device__ __forceinline__ float tile_mma_presplit_seq(const SplitSeq& p, unsigned char* __restrict__ lds, TileAcc& acc) {
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    constexpr int NSL = 128 / SPLIT_KS;                // slices per product
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    lds_byte* l0 = (lds_byte*)lds;
+    unsigned a_addr[2], b_addr[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        a_addr[q] = (unsigned)split_plane_offset(wm * 64 + q * 32 + lm, h);
+        b_addr[q] = (unsigned)(2 * PRE_BLOCK + split_plane_offset(wn * 64 + q * 32 + lm, h));
+    }
+    const int nst = p.n * NSL;
+    const unsigned lane_off = (unsigned)(wave * 1024 + lane * 16);   // this lane's 16 bytes inside every block
+    auto issue = [&](int s, int buf) {
+        const int sc = s < nst ? s : nst - 1;          // past the end: re-read the last slice (never consumed)
+        const int q = sc / NSL, ks = sc - q * NSL;
+        const KFAC_AS1 unsigned char* pa = p.a_blk(q);
+        const KFAC_AS1 unsigned char* pb = p.b_blk(q);
+        const KFAC_AS1 unsigned char* src[4] = {pa, pa + p.a_plane(), pb, pb + p.b_plane()};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ks * PRE_BLOCK + lane_off),
+                                             (__attribute__((address_space(3))) void*)(l0 + buf * PRE_STAGE + j * PRE_BLOCK + wave * 1024),
+                                             16, 0, 0);
+    };
+    float back = 1.0f;
+#pragma unroll
+    for (int s = 0; s < PRE_NS - 1; ++s) issue(s, s);
+    for (int it = 0; it < nst; it += PRE_NS) {
+#pragma unroll
+        for (int bi = 0; bi < PRE_NS; ++bi) {
+            const int s = it + bi;
+            if (s >= nst) break;                                            // uniform
+            static_assert(PRE_NS == 3, "the wait below counts (PRE_NS - 2) * 4 younger copies");
+            asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");   // slice s landed (everybody's part)
+            issue(s + PRE_NS - 1, (bi + PRE_NS - 1) % PRE_NS);               // refill the slot slice s - 1 vacated
+            if (s % NSL == 0) {                                              // uniform: a new product begins
+                const float sq = p.scale_of(s / NSL);
                 const float f = sq * back;
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)

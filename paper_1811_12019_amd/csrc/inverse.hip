@@ -558,17 +558,6 @@ constexpr int PANEL_RLD = NB + 4;          // LDS row stride when the stage is r
 constexpr int PANEL_LDS_FLOATS = NB * PANEL_RLD;
 static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
 
-// largest magnitude over the workgroup (every thread gets it); red: 4 floats of LDS
-__device__ __forceinline__ float block_absmax(float x, float* __restrict__ red) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
-    __syncthreads();
-    x = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    return x;
-}
-
 __global__ __launch_bounds__(256) void inv_panel_kernel(Batch b) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
     __shared__ float red[4];

@@ -1,11 +1,21 @@
 // Preconditioned gradient P = Ginv . gradW . Ainv  (Eq. 7 written for the d_G x d_A weight-gradient matrix;
-// Algorithm 1 stage 5), fp32 on the matrix cores.
+// Algorithm 1 stage 5), fp32 results from the fp16 matrix cores.
 //
-// Both products run as "NT" tile products (both operands K-contiguous), using the symmetry of the inverses:
+// Both products run as "NT" tile products (both operands contiguous along the contraction index), using the symmetry
+// of the inverses:
 //   Yt[dA x dG] = Ainv . gradW^T      Yt[j, i] = sum_k Ainv[j, k] gradW[i, k]
 //   P [dG x dA] = Ginv . Yt^T         P [i, j] = sum_k Ginv[i, k] Yt[j, k]
-// A batch of layers runs as two launches (one per product) over the tiles of all layers together, so that the
-// many small layers fill the machine; the workgroup -> (layer, tile) map is a prefix table in the kernel arguments.
+// Every fp32 operand is first cut into 128 x 128 blocks, each scaled by a power of two of its own (largest magnitude
+// -> about 1) and split into two fp16 pieces (22 significant bits together), stored as planes in the order the tile
+// product wants them in LDS (gemm_split.h): one pass over the inverses and the gradient (pre_split_kernel), and the
+// first product's epilogue writes Yt in the same form.  The tile products then do no conversion work at all: operand
+// slices go from global memory to LDS by DMA, and each 128-long piece of the contraction is three fp16 MFMAs per
+// 32 x 32 block (high x high + high x low + low x high), the accumulators following the blocks' scales exactly.
+// Splitting inside the product instead (three bf16 pieces of every operand, by every tile that reads it) kept the
+// vector ALUs and LDS busier than the matrix cores.
+// A batch of layers runs as three launches (split, product 1, product 2) over the blocks / tiles of all layers
+// together, so that the many small layers fill the machine; the workgroup -> (layer, tile) map is a prefix table in
+// the kernel arguments.
 #include <algorithm>
 
 #include "gemm_split.h"
@@ -22,32 +32,129 @@ struct PBatch {
     short order[PMAXB];               // launch position -> item (relative to first): longest contraction first
 };
 
-// phase 1: Yt[dA x dG] = Ainv . gradW^T      phase 2: out[dG x dA] = Ginv . Yt^T
-__global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[split_lds_bytes<3>()];
+// Where a layer's operand planes live in its scratch.  A matrix of r x k elements is held as ceil(r / 128) slabs of
+// ceil(k / 128) blocks of 128 x 128 (zero padded), block (s, c) at ((s * chunks + c) * PRE_SLAB) in the high plane and
+// in the low plane that follows it, with one scale per block.
+struct PlaneLayout {
+    int nA, nG;                       // 128-blocks along d_A, d_G
+    size_t a_hi, g_hi, w_hi, y_hi;    // byte offsets of the high planes of Ainv, Ginv, gradW (dG x dA), Yt (dA x dG)
+    size_t a_plane, g_plane, w_plane, y_plane;   // bytes of one plane of each
+    size_t a_sc, g_sc, w_sc, y_sc;    // byte offsets of the scale arrays
+    size_t bytes;
+};
+
+static inline __host__ __device__ PlaneLayout plane_layout(int dG, int dA) {
+    PlaneLayout L;
+    L.nA = (dA + TM - 1) / TM; L.nG = (dG + TM - 1) / TM;
+    L.a_plane = (size_t)L.nA * L.nA * PRE_SLAB;
+    L.g_plane = (size_t)L.nG * L.nG * PRE_SLAB;
+    L.w_plane = (size_t)L.nG * L.nA * PRE_SLAB;
+    L.y_plane = L.w_plane;
+    L.a_hi = 0;
+    L.g_hi = L.a_hi + 2 * L.a_plane;
+    L.w_hi = L.g_hi + 2 * L.g_plane;
+    L.y_hi = L.w_hi + 2 * L.w_plane;
+    L.a_sc = L.y_hi + 2 * L.y_plane;
+    L.g_sc = L.a_sc + sizeof(float) * L.nA * L.nA;
+    L.w_sc = L.g_sc + sizeof(float) * L.nG * L.nG;
+    L.y_sc = L.w_sc + sizeof(float) * L.nG * L.nA;
+    L.bytes = L.y_sc + sizeof(float) * L.nA * L.nG;
+    return L;
+}
+
+__device__ __forceinline__ kfac_precond_item locate_item(const PBatch& b, int wg, int& local) {
     int lo = 0, hi = b.count;
-    const int wg = blockIdx.x;
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
         if (b.prefix[mid] <= wg) lo = mid; else hi = mid;
     }
-    const kfac_precond_item it = b.table ? b.table[b.first + b.order[lo]] : b.single;
-    const int local = wg - b.prefix[lo];
-    const gfloat *A, *B;
-    gfloat* C;
-    int M, N, K;
-    if (phase == 1) { A = as_global(it.Ainv); B = as_global(it.gradW); C = as_global((float*)it.ws); M = it.dA; N = it.dG; K = it.dA; }
-    else            { A = as_global(it.Ginv); B = as_global((const float*)it.ws); C = as_global(it.out); M = it.dG; N = it.dA; K = it.dG; }
+    local = wg - b.prefix[lo];
+    return b.table ? b.table[b.first + b.order[lo]] : b.single;
+}
+
+// 128 rows (row0 ..) x 128 columns of fp32 values held one float4 per thread and pass (thread t: columns 4 (t % 32) ..,
+// rows t / 32 + 8 p) -> the block's scale and its two piece planes.
+__device__ __forceinline__ void emit_block(const v4f (&v)[16], KFAC_AS1 unsigned char* hi, size_t plane, gfloat* scale,
+                                           float* red) {
+    const int t = threadIdx.x, c4 = (t & 31) * 4, rr = t >> 5;
+    float m = 0.f;
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m = fmaxf(m, fabsf(v[p][i]));
+    const float sc = panel_scale(block_absmax(m, red));
+    if (t == 0) *scale = sc;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) store_split4_h2(hi, hi + plane, rr + 8 * p, c4, v[p] * sc);
+}
+
+// One 128 x 128 block of Ainv, Ginv or gradW per workgroup.
+__global__ __launch_bounds__(256) void pre_split_kernel(PBatch b) {
+    __shared__ float red[4];
+    int local;
+    const kfac_precond_item it = locate_item(b, blockIdx.x, local);
+    const PlaneLayout L = plane_layout(it.dG, it.dA);
+    KFAC_AS1 unsigned char* ws = (KFAC_AS1 unsigned char*)as_global((float*)it.ws);
+    const gfloat* X;
+    int rows, cols, chunks;
+    size_t hi, plane, sc;
+    if (local < L.nA * L.nA) {
+        X = as_global(it.Ainv); rows = cols = it.dA; chunks = L.nA; hi = L.a_hi; plane = L.a_plane; sc = L.a_sc;
+    } else if ((local -= L.nA * L.nA) < L.nG * L.nG) {
+        X = as_global(it.Ginv); rows = cols = it.dG; chunks = L.nG; hi = L.g_hi; plane = L.g_plane; sc = L.g_sc;
+    } else {
+        local -= L.nG * L.nG;
+        X = as_global(it.gradW); rows = it.dG; cols = it.dA; chunks = L.nA; hi = L.w_hi; plane = L.w_plane; sc = L.w_sc;
+    }
+    const int s = local / chunks, c = local - s * chunks;
+    const int r0 = s * TM, k0 = c * TM;
+    const int t = threadIdx.x, c4 = (t & 31) * 4, rr = t >> 5;
+    v4f v[16];
+    if (r0 + TM <= rows && k0 + TM <= cols) {            // all loads go out together (a guard per load would serialise them)
+#pragma unroll
+        for (int p = 0; p < 16; ++p) v[p] = *(const KFAC_AS1 v4f_a4*)(X + (size_t)(r0 + rr + 8 * p) * cols + k0 + c4);
+    } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + rr + 8 * p;
+            v[p] = load4_guard(X + (size_t)(row < rows ? row : 0) * cols, row < rows, k0 + c4, cols);
+        }
+    }
+    emit_block(v, ws + hi + (size_t)local * PRE_SLAB, plane, (gfloat*)(ws + sc) + local, red);
+}
+
+// phase 1: Yt[dA x dG] = Ainv . gradW^T (written as planes)      phase 2: out[dG x dA] = Ginv . Yt^T
+__global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[PRE_NS * PRE_STAGE];
+    __shared__ float sc[256];
+    __shared__ float red[4];
+    int local;
+    const kfac_precond_item it = locate_item(b, blockIdx.x, local);
+    const PlaneLayout L = plane_layout(it.dG, it.dA);
+    KFAC_AS1 unsigned char* ws = (KFAC_AS1 unsigned char*)as_global((float*)it.ws);
     // Workgroups go to the 8 XCDs round-robin, each with an L2 of its own.  Inside a block of 8 tile rows, the eight
-    // XCDs take one tile row each and walk along it: the tiles that share an A panel (128 rows of the inverse, the
-    // large operand when K is long) run on one L2, side by side, instead of on all eight (a third less traffic
-    // beyond L2).
-    const int tm = (M + TM - 1) / TM, tn = (N + TM - 1) / TM;
+    // XCDs take one tile row each and walk along it: the tiles that share an A slab (128 rows of the inverse, the
+    // large operand when the contraction is long) run on one L2, side by side, instead of on all eight.
+    const int tm = phase == 1 ? L.nA : L.nG, tn = phase == 1 ? L.nG : L.nA;
     const int blk = local / (8 * tn), within = local - blk * 8 * tn;
     const int rb = min(8, tm - 8 * blk);
     const int ti = 8 * blk + within % rb, tj = within / rb;
-    const int i0 = ti * TM, j0 = tj * TM;
-    const int irows = min(TM, M - i0), jrows = min(TM, N - j0);
+    SplitSeq run;
+    const gfloat *sa, *sb;
+    if (phase == 1) {
+        run.n = L.nA;
+        run.a_hi = ws + L.a_hi + (size_t)ti * L.nA * PRE_SLAB; run.plane_a = L.a_plane;
+        run.b_hi = ws + L.w_hi + (size_t)tj * L.nA * PRE_SLAB; run.plane_b = L.w_plane;
+        sa = (const gfloat*)(ws + L.a_sc) + ti * L.nA; sb = (const gfloat*)(ws + L.w_sc) + tj * L.nA;
+    } else {
+        run.n = L.nG;
+        run.a_hi = ws + L.g_hi + (size_t)ti * L.nG * PRE_SLAB; run.plane_a = L.g_plane;
+        run.b_hi = ws + L.y_hi + (size_t)tj * L.nG * PRE_SLAB; run.plane_b = L.y_plane;
+        sa = (const gfloat*)(ws + L.g_sc) + ti * L.nG; sb = (const gfloat*)(ws + L.y_sc) + tj * L.nG;
+    }
+    run.scale_lds = sc;
+    const int t = threadIdx.x;
+    if (t < run.n) sc[t] = sa[t] * sb[t];                // (at most 256 blocks along a contraction: dimensions end at 32768)
     TileAcc acc;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -55,27 +162,66 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc.c[mb][nb][r] = 0.f;
-    // Interior tiles take the contraction 128 columns at a time through the unrolled, branch-free pipeline (two slabs
-    // of look-ahead with exact wait counts; the general loop has one slab of look-ahead and pays a memory round trip
-    // per slab, which a long contraction with few tiles cannot hide); the rest of K, and edge tiles, go the general way.
-    const gfloat* At = A + (size_t)i0 * K;
-    const gfloat* Bt = B + (size_t)j0 * K;
-    int kdone = 0;
-    if (irows == TM && jrows == TM) {
-        for (; kdone + 128 <= K; kdone += 128)
-            tile_mma_nt_split<3, false, 128 / SPLIT_KS, true>(At + kdone, K, TM, Bt + kdone, K, TM, 128, lds, acc);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // (the product counts its own copies in flight)
+    __syncthreads();
+    const float back = tile_mma_presplit_seq(run, lds, acc);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc.c[mb][nb] *= back;
+    const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    if (phase == 2) {
+        gfloat* C = as_global(it.out);
+        const int i0 = ti * TM, j0 = tj * TM;
+        const int irows = min(TM, it.dG - i0), jrows = min(TM, it.dA - j0);
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nb, lane);
+                    if (row < irows && col < jrows) C[(size_t)(i0 + row) * it.dA + j0 + col] = acc.c[mb][nb][r];
+                }
+        return;
     }
-    if (kdone < K) tile_mma_nt_split<3>(At + kdone, K, irows, Bt + kdone, K, jrows, K - kdone, lds, acc);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    // Yt block (slab ti, chunk tj) leaves as scaled fp16 pieces: through LDS, 64 rows at a time, so that a thread holds
+    // four consecutive values of a row (rows and columns beyond the matrix are exact zeros: their operands were).
+    float m = 0.f;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nb, lane);
-                if (row < irows && col < jrows) C[(size_t)(i0 + row) * N + j0 + col] = acc.c[mb][nb][r];
-            }
+            for (int r = 0; r < 16; ++r) m = fmaxf(m, fabsf(acc.c[mb][nb][r]));
+    const float sy = panel_scale(block_absmax(m, red));
+    const int blkidx = ti * L.nG + tj;
+    if (t == 0) ((gfloat*)(ws + L.y_sc))[blkidx] = sy;
+    KFAC_AS1 unsigned char* yh = ws + L.y_hi + (size_t)blkidx * PRE_SLAB;
+    constexpr int RLD = TM + 4;
+    float* stage = (float*)lds;
+    static_assert(64 * RLD * 4 <= PRE_NS * PRE_STAGE, "half a tile fits the ring's memory");
+    const int c4 = (t & 31) * 4, rr = t >> 5;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        if (half == 1) __syncthreads();
+        if (wm == half) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        stage[(acc_row(0, mb, r, lane)) * RLD + acc_col(wn, nb, lane)] = acc.c[mb][nb][r];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int row = rr + 8 * p;
+            const v4f x = *(const v4f*)&stage[row * RLD + c4];
+            store_split4_h2(yh, yh + L.y_plane, half * 64 + row, c4, x * sy);
+        }
+    }
 }
 
 static inline int tiles_of(int M, int N) { return ceil_div(M, TM) * ceil_div(N, TM); }
@@ -87,6 +233,14 @@ static int run_group(const kfac_precond_item* host, const kfac_precond_item* dev
     b.first = first;
     b.count = count;
     if (!dev) b.single = host[first];
+    // the operands' piece planes: one workgroup per 128 x 128 block of Ainv, Ginv and gradW
+    b.prefix[0] = 0;
+    for (int i = 0; i < count; ++i) {
+        b.order[i] = (short)i;
+        const int nA = ceil_div(host[first + i].dA, TM), nG = ceil_div(host[first + i].dG, TM);
+        b.prefix[i + 1] = b.prefix[i] + nA * nA + nG * nG + nG * nA;
+    }
+    KFAC_LAUNCH(pre_split_kernel, dim3(b.prefix[count]), dim3(256), stream, b);
     for (int phase = 1; phase <= 2; ++phase) {
         // tiles with the longest contraction (K = dA in phase 1, dG in phase 2) go first: workgroups are dispatched in
         // order, so the long ones start early and the short ones fill the tail
@@ -119,7 +273,7 @@ using namespace kfac;
 
 extern "C" size_t kfac_precondition_workspace_bytes(int32_t dG, int32_t dA) {
     if (dG <= 0 || dA <= 0 || dG > 32768 || dA > 32768) return 0;
-    return align_up((size_t)dG * dA * sizeof(float), 256);
+    return align_up(plane_layout(dG, dA).bytes, 256);
 }
 
 extern "C" int kfac_precondition(const float* Ginv, const float* Ainv, const float* gradW, int32_t dG, int32_t dA,

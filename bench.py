@@ -32,8 +32,8 @@ from paper_1811_12019_amd import synth                # noqa: E402
 
 PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, TFLOP/s, GB/s
 # fp32 products computed as sums of 16-bit MFMAs over split operands: 6 MFMAs per fp32 product with both operands
-# split into three bf16 pieces (the sweep's panel product), 3 with both split two ways (two bf16 pieces:
-# preconditioning; two fp16 pieces of scaled operands: the sweep's rank-128 updates); fp16 and bf16 MFMA peaks are equal
+# split into three bf16 pieces (the sweep's panel product), 3 with both split into two fp16 pieces of scaled operands
+# (the sweep's rank-128 updates, both preconditioning products); fp16 and bf16 MFMA peaks are equal
 PEAK["mfma_bf16x3"] = round(PEAK["mfma_bf16"] / 6, 1)
 PEAK["mfma_f16x2"] = round(PEAK["mfma_bf16"] / 3, 1)
 
@@ -60,7 +60,9 @@ def kernel_work(net: kstep.KfacNetworkStep):
         # flops (fp32 matrix cores), panel products of 2 d nb^2 (bf16 matrix cores, operands split three ways)
         "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_first_pivot_flops(d) for d in dims)),
         "inv_panel_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
-        "gemm_nt_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
+        "gemm_nt_kernel": ("mfma", PEAK["mfma_f16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
+        # the operands' piece planes: every element of both inverses and of the gradient read (4 B) and written (2 x 2 B)
+        "pre_split_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(8.0 * (s.d_A * s.d_A + s.d_G * s.d_G + s.d_G * s.d_A) for s in shapes)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),
         "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),
@@ -260,7 +262,8 @@ def run_cfg4(args):
 
 # what each stage computes in (the whole path stores and accumulates in fp32)
 DTYPE = ("bf16 factor inputs (exact products, f32 accumulate); f32 storage; inverse products on 16-bit matrix cores from "
-         "f32 operands split into 3 bf16 (panel) / 2 scaled f16 (rank-128 updates) pieces; preconditioning from 3 bf16 pieces")
+         "f32 operands split into 3 bf16 (panel) / 2 scaled f16 (rank-128 updates) pieces; preconditioning products from "
+         "2 f16 pieces of operands scaled per 128x128 block")
 
 
 def main():

@@ -241,7 +241,14 @@ typedef struct kfac_inverse_item {
     float damping;
     const float* damping_dev;  /* NULL, or a device float that replaces `damping` (read when the work runs: the
                                   value may come from kfac_pi_damping_batched enqueued before on the same stream) */
+    void* planes;       /* NULL, or kfac_inverse_planes_bytes(dim) bytes (device, 256-byte aligned) that receive
+                           the inverse a second time in the form the preconditioning products multiply from: 128 x 128
+                           blocks, scaled by one power of two, as two planes of fp16 pieces (see
+                           kfac_precond_item.Ginv_planes).  Needs damping > 0 and a positive semidefinite S: the scale
+                           is chosen from the bound 1 / damping on the inverse's entries.  Minv is written as always. */
 } kfac_inverse_item;
+
+size_t kfac_inverse_planes_bytes(int32_t dim);
 
 int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, int32_t count, void* stream);
 
@@ -291,6 +298,9 @@ typedef struct kfac_precond_item {
     float* out;          /* dG x dA (device) */
     void* ws;            /* per-layer scratch (device, 256-byte aligned) */
     int32_t dG, dA;
+    const void* Ginv_planes;   /* NULL, or the planes kfac_damped_inverse_batched wrote for Ginv (kfac_inverse_item.planes): */
+    const void* Ainv_planes;   /* the call then multiplies from them instead of splitting Ginv / Ainv itself (the fp32
+                                  matrices are not read); they must belong to the same inverses */
 } kfac_precond_item;
 
 int kfac_precondition_batched(const kfac_precond_item* items_host, const kfac_precond_item* items_dev,

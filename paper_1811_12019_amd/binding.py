@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = (
     "kfac_weight_update_workspace_bytes", "kfac_weight_update_batched",
     "kfac_bn_sample_grads_workspace_bytes", "kfac_bn_sample_grads", "kfac_bn_diag_precondition",
     "kfac_bn_sample_grads_batched_workspace_bytes", "kfac_bn_sample_grads_batched",
-    "kfac_inverse_workspace_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
+    "kfac_inverse_workspace_bytes", "kfac_inverse_planes_bytes", "kfac_damped_inverse", "kfac_damped_inverse_batched",
     "kfac_pi_damping_batched", "kfac_warmup_damping_alpha", "kfac_warmup_damping_next", "kfac_bn_damping",
     "kfac_refresh_interval",
     "kfac_precondition_workspace_bytes", "kfac_precondition", "kfac_precondition_batched",
@@ -80,7 +80,8 @@ class kfac_update_item(ctypes.Structure):
 
 class kfac_inverse_item(ctypes.Structure):
     _fields_ = [("S", ctypes.c_void_p), ("Minv", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("info", ctypes.c_void_p),
-                ("dim", ctypes.c_int32), ("damping", ctypes.c_float), ("damping_dev", ctypes.c_void_p)]
+                ("dim", ctypes.c_int32), ("damping", ctypes.c_float), ("damping_dev", ctypes.c_void_p),
+                ("planes", ctypes.c_void_p)]
 
 
 class kfac_pi_item(ctypes.Structure):
@@ -89,7 +90,8 @@ class kfac_pi_item(ctypes.Structure):
 
 class kfac_precond_item(ctypes.Structure):
     _fields_ = [("Ginv", ctypes.c_void_p), ("Ainv", ctypes.c_void_p), ("gradW", ctypes.c_void_p),
-                ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("dG", ctypes.c_int32), ("dA", ctypes.c_int32)]
+                ("out", ctypes.c_void_p), ("ws", ctypes.c_void_p), ("dG", ctypes.c_int32), ("dA", ctypes.c_int32),
+                ("Ginv_planes", ctypes.c_void_p), ("Ainv_planes", ctypes.c_void_p)]
 
 
 class KfacError(RuntimeError):
@@ -156,6 +158,8 @@ def load_library() -> ctypes.CDLL:
     lib.kfac_bn_diag_precondition.argtypes = [vp, i32, i32, vp, f32, vp, vp, vp]
     lib.kfac_inverse_workspace_bytes.restype = sz
     lib.kfac_inverse_workspace_bytes.argtypes = [i32]
+    lib.kfac_inverse_planes_bytes.restype = sz
+    lib.kfac_inverse_planes_bytes.argtypes = [i32]
     lib.kfac_damped_inverse.restype = ctypes.c_int
     lib.kfac_damped_inverse.argtypes = [vp, i32, f32, vp, vp, vp, sz, vp]
     lib.kfac_damped_inverse_batched.restype = ctypes.c_int
@@ -476,8 +480,10 @@ class InverseBatch:
 
     def __init__(self, S: Sequence[torch.Tensor], Minv: Sequence[torch.Tensor], dampings: Sequence[float],
                  info: Optional[torch.Tensor] = None, device="cuda",
-                 dampings_dev: Optional[Sequence[Optional[int]]] = None, ws=None):
+                 dampings_dev: Optional[Sequence[Optional[int]]] = None, ws=None, planes=None):
         """dampings_dev[i]: None, or the device address of a float that replaces dampings[i] when the work runs.
+        planes: None, or per matrix None / a byte tensor of kfac_inverse_planes_bytes(dim) that receives the inverse as
+        fp16 piece planes (what PrecondBatch takes as Ginv_planes / Ainv_planes).
         ws: None (scratch is allocated here), or one scratch tensor per matrix of kfac_inverse_workspace_bytes(dim)
         bytes, which tables that never run at the same time may share."""
         n = len(S)
@@ -486,13 +492,18 @@ class InverseBatch:
         self.count = n
         self.ws = list(ws) if ws is not None else [alloc_workspace(kfac_inverse_workspace_bytes(d), device) for d in dims]
         self.info = info if info is not None else torch.zeros(n, dtype=torch.int32, device=device)
-        self.keep = (list(S), list(Minv))
+        self.keep = (list(S), list(Minv), None if planes is None else list(planes))
         arr = (kfac_inverse_item * n)()
         for slot, i in enumerate(self.order):
             arr[slot] = kfac_inverse_item(S[i].data_ptr(), Minv[i].data_ptr(), _ptr(self.ws[i]),
                                           self.info.data_ptr() + 4 * i, dims[i], float(dampings[i]),
-                                          None if dampings_dev is None else dampings_dev[i])
+                                          None if dampings_dev is None else dampings_dev[i],
+                                          None if planes is None else _ptr(planes[i]))
         self.host = arr
+
+
+def kfac_inverse_planes_bytes(dim: int) -> int:
+    return int(load_library().kfac_inverse_planes_bytes(int(dim)))
 
 
 def kfac_damped_inverse_batched(batch: InverseBatch, stream=None) -> None:
@@ -561,18 +572,21 @@ class PrecondBatch:
     allocated here), or one scratch tensor per layer of kfac_precondition_workspace_bytes(d_G, d_A) bytes."""
 
     def __init__(self, Ginv: Sequence[torch.Tensor], Ainv: Sequence[torch.Tensor], gradW: Sequence[torch.Tensor],
-                 out: Sequence[torch.Tensor], device="cuda", ws=None):
+                 out: Sequence[torch.Tensor], device="cuda", ws=None, Ginv_planes=None, Ainv_planes=None):
+        """Ginv_planes / Ainv_planes: None, or per layer None / the planes tensor an InverseBatch filled for that inverse."""
         n = len(out)
         shapes = [tuple(g.shape) for g in gradW]
         self.order = sorted(range(n), key=lambda i: -shapes[i][1])       # large d_A first: best load balance
         self.count = n
         self.ws = (list(ws) if ws is not None else
                    [alloc_workspace(kfac_precondition_workspace_bytes(dG, dA), device) for dG, dA in shapes])
-        self.keep = (list(Ginv), list(Ainv), list(gradW), list(out))
+        self.keep = (list(Ginv), list(Ainv), list(gradW), list(out), Ginv_planes, Ainv_planes)
         arr = (kfac_precond_item * n)()
         for slot, i in enumerate(self.order):
             arr[slot] = kfac_precond_item(Ginv[i].data_ptr(), Ainv[i].data_ptr(), gradW[i].data_ptr(),
-                                          out[i].data_ptr(), self.ws[i].data_ptr(), shapes[i][0], shapes[i][1])
+                                          out[i].data_ptr(), self.ws[i].data_ptr(), shapes[i][0], shapes[i][1],
+                                          None if Ginv_planes is None else _ptr(Ginv_planes[i]),
+                                          None if Ainv_planes is None else _ptr(Ainv_planes[i]))
         self.host = arr
         self.dev = torch.frombuffer(bytearray(bytes(arr)), dtype=torch.uint8).to(device)
 

@@ -91,6 +91,21 @@ __device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& loca
 
 static inline __host__ __device__ int nblk_of(int dim) { return (dim + NB - 1) / NB; }
 static inline __host__ __device__ int ldw_of(int dim) { return (dim + 31) / 32 * 32; }
+
+// Optional second form of the result, for the products that consume the inverse (preconditioning): the matrix cut
+// into 128 x 128 blocks (zero padded), every element scaled by one power of two and split into two fp16 pieces, as two
+// planes of n x n blocks in the layout of gemm_split.h (block (s, c) at (s n + c) PRE_SLAB bytes) followed by n x n
+// floats that all hold the scale.  The scale: the damped matrix is S + lambda I with S positive semidefinite, so no
+// entry of the inverse exceeds 1 / lambda in magnitude; 2^(8 + floor(log2 lambda)) maps that bound to at most 2^8, which
+// leaves fp16's range seven more binades before overflow and keeps all 22 bits of entries down to 2^-11 of the bound
+// (smaller ones lose bits only below 2^-33 of it).
+static inline __host__ __device__ size_t inverse_plane_bytes(int dim) { return (size_t)nblk_of(dim) * nblk_of(dim) * PRE_SLAB; }
+static inline __host__ __device__ size_t inverse_planes_bytes(int dim) {
+    return 2 * inverse_plane_bytes(dim) + sizeof(float) * nblk_of(dim) * nblk_of(dim);
+}
+__device__ __forceinline__ float inverse_plane_scale(float damping) {
+    return damping > 0.f ? ldexpf(1.0f, 8 + ilogbf(damping)) : 1.0f;
+}
 // Steps are taken in groups of up to GM consecutive blocks, none of them the matrix's last.  Inside a group only the
 // tiles that the group's remaining pivots and panels need are kept up to date step by step (block rows / columns of
 // the blocks still to come, all of them short lists: "narrow" launches); every other tile receives the group's
@@ -1212,6 +1227,71 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     else upd_regular<true>(c, ws.U(cur), lds);
 }
 
+// The piece planes of finished inverses: one workgroup per 128 x 128 block, read from the caller's output after the
+// matrix's last step.  (Written by the last step's tiles themselves the planes cost the update kernel registers that
+// its hot paths miss, and more time than this pass over the output.)
+constexpr int PLMAXB = 100;
+struct PlanesBatch {
+    int count;
+    int prefix[PLMAXB + 1];           // block prefix sums
+    int dim[PLMAXB];
+    float damping[PLMAXB];
+    const float* damping_dev[PLMAXB];
+    const float* Minv[PLMAXB];
+    void* planes[PLMAXB];
+};
+static_assert(sizeof(PlanesBatch) <= 4096, "the batch travels in the kernel arguments");
+
+__global__ __launch_bounds__(256) void inv_planes_kernel(PlanesBatch b) {
+    const int t = threadIdx.x;
+    const int m = __syncthreads_count(t < b.count - 1 && b.prefix[t + 1] <= (int)blockIdx.x);
+    const int blk = blockIdx.x - b.prefix[m];
+    const int d = b.dim[m], n = nblk_of(d);
+    const int s = blk / n, c = blk - s * n;
+    const int r0 = s * NB, k0 = c * NB;
+    const float lam = b.damping_dev[m] ? *as_global(b.damping_dev[m]) : b.damping[m];
+    const float sc = inverse_plane_scale(lam);
+    const gfloat* X = as_global(b.Minv[m]);
+    KFAC_AS1 unsigned char* planes = (KFAC_AS1 unsigned char*)as_global((float*)b.planes[m]);
+    const size_t plane = inverse_plane_bytes(d);
+    if (t == 0) ((gfloat*)(planes + 2 * plane))[blk] = sc;
+    const int c4 = (t & 31) * 4, rr = t >> 5;
+    v4f v[16];
+    if (r0 + NB <= d && k0 + NB <= d) {                 // all loads go out together (a guard per load would serialise them)
+#pragma unroll
+        for (int p = 0; p < 16; ++p) v[p] = *(const KFAC_AS1 v4f_a4*)(X + (size_t)(r0 + rr + 8 * p) * d + k0 + c4);
+    } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = r0 + rr + 8 * p;
+            v[p] = load4_guard(X + (size_t)(row < d ? row : 0) * d, row < d, k0 + c4, d);
+        }
+    }
+    KFAC_AS1 unsigned char* dst = planes + (size_t)blk * PRE_SLAB;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) store_split4_h2(dst, dst + plane, rr + 8 * p, c4, v[p] * sc);
+}
+
+// Planes for the matrices of a call that asked for them (after all their steps have been enqueued on `stream`).
+static int write_planes(const kfac_inverse_item* h, int count, hipStream_t stream) {
+    PlanesBatch b;
+    b.count = 0;
+    b.prefix[0] = 0;
+    for (int i = 0; i <= count; ++i) {
+        if (i < count && h[i].planes) {
+            const int k = b.count++;
+            b.dim[k] = h[i].dim; b.damping[k] = h[i].damping; b.damping_dev[k] = h[i].damping_dev;
+            b.Minv[k] = h[i].Minv; b.planes[k] = h[i].planes;
+            b.prefix[k + 1] = b.prefix[k] + nblk_of(h[i].dim) * nblk_of(h[i].dim);
+        }
+        if (b.count == PLMAXB || (i == count && b.count > 0)) {
+            KFAC_LAUNCH(inv_planes_kernel, dim3(b.prefix[b.count]), dim3(256), stream, b);
+            b.count = 0;
+        }
+    }
+    return KFAC_OK;
+}
+
 static inline int tri_tiles(int dim) { int n = nblk_of(dim); return n * (n + 1) / 2; }
 
 static void fill_batch(Batch& b, const kfac_inverse_item* items, int count) {
@@ -1285,6 +1365,7 @@ static bool item_ok(const kfac_inverse_item& it) {
     if (!it.S || !it.Minv || it.dim <= 0 || it.dim > 32768) return false;
     if (it.S == it.Minv) return false;
     if (nblk_of(it.dim) > 1 && (!it.ws || ((uintptr_t)it.ws & 255))) return false;
+    if (it.planes && (((uintptr_t)it.planes & 255) || (!it.damping_dev && !(it.damping > 0.f)))) return false;
     return true;
 }
 
@@ -1297,10 +1378,16 @@ extern "C" size_t kfac_inverse_workspace_bytes(int32_t dim) {
     return ws_bytes_of(dim);
 }
 
+extern "C" size_t kfac_inverse_planes_bytes(int32_t dim) {
+    if (dim <= 0 || dim > 32768) return 0;
+    return align_up(inverse_planes_bytes(dim), 256);
+}
+
 extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, float* Minv, int32_t* info,
                                    void* ws, size_t ws_bytes, void* stream) {
     kfac_inverse_item it;
     it.S = S; it.Minv = Minv; it.ws = ws; it.info = info; it.dim = dim; it.damping = damping; it.damping_dev = nullptr;
+    it.planes = nullptr;
     if (dim <= 0 || dim > 32768 || !S || !Minv || S == Minv) return KFAC_ERR_INVALID_ARG;
     if (nblk_of(dim) > 1) {
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < ws_bytes_of(dim)) return KFAC_ERR_WORKSPACE;
@@ -1324,5 +1411,5 @@ extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, 
         int rc = run_group(sel, n, (hipStream_t)stream);
         if (rc != KFAC_OK) return rc;
     }
-    return KFAC_OK;
+    return write_planes(items_host, count, (hipStream_t)stream);
 }

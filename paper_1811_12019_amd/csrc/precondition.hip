@@ -32,35 +32,50 @@ struct PBatch {
     short order[PMAXB];               // launch position -> item (relative to first): longest contraction first
 };
 
-// Where a layer's operand planes live in its scratch.  A matrix of r x k elements is held as ceil(r / 128) slabs of
-// ceil(k / 128) blocks of 128 x 128 (zero padded), block (s, c) at ((s * chunks + c) * PRE_SLAB) in the high plane and
-// in the low plane that follows it, with one scale per block.
+// A matrix of r x k elements as planes: ceil(r / 128) slabs of ceil(k / 128) blocks of 128 x 128 (zero padded), block
+// (s, c) at ((s * chunks + c) * PRE_SLAB) bytes in the plane of high pieces and in the plane of low pieces that
+// follows it, then one float per block: its scale.  The four plane sets of a layer (Ainv, Ginv, gradW: dG x dA, Yt:
+// dA x dG) live one after the other in its scratch; the inverses' may instead be the ones the inversion wrote.
+struct PlaneSet {
+    KFAC_AS1 unsigned char* hi;
+    size_t plane;                     // bytes of one plane
+    __device__ __forceinline__ gfloat* scales() const { return (gfloat*)(hi + 2 * plane); }
+};
 struct PlaneLayout {
     int nA, nG;                       // 128-blocks along d_A, d_G
-    size_t a_hi, g_hi, w_hi, y_hi;    // byte offsets of the high planes of Ainv, Ginv, gradW (dG x dA), Yt (dA x dG)
-    size_t a_plane, g_plane, w_plane, y_plane;   // bytes of one plane of each
-    size_t a_sc, g_sc, w_sc, y_sc;    // byte offsets of the scale arrays
+    size_t a_plane, g_plane, w_plane; // bytes of one plane of Ainv, Ginv, gradW (= Yt)
+    size_t a_off, g_off, w_off, y_off;
     size_t bytes;
 };
-
+static inline __host__ __device__ size_t plane_set_bytes(size_t plane, int blocks) {
+    return (2 * plane + sizeof(float) * blocks + 255) & ~(size_t)255;
+}
 static inline __host__ __device__ PlaneLayout plane_layout(int dG, int dA) {
     PlaneLayout L;
     L.nA = (dA + TM - 1) / TM; L.nG = (dG + TM - 1) / TM;
     L.a_plane = (size_t)L.nA * L.nA * PRE_SLAB;
     L.g_plane = (size_t)L.nG * L.nG * PRE_SLAB;
     L.w_plane = (size_t)L.nG * L.nA * PRE_SLAB;
-    L.y_plane = L.w_plane;
-    L.a_hi = 0;
-    L.g_hi = L.a_hi + 2 * L.a_plane;
-    L.w_hi = L.g_hi + 2 * L.g_plane;
-    L.y_hi = L.w_hi + 2 * L.w_plane;
-    L.a_sc = L.y_hi + 2 * L.y_plane;
-    L.g_sc = L.a_sc + sizeof(float) * L.nA * L.nA;
-    L.w_sc = L.g_sc + sizeof(float) * L.nG * L.nG;
-    L.y_sc = L.w_sc + sizeof(float) * L.nG * L.nA;
-    L.bytes = L.y_sc + sizeof(float) * L.nA * L.nG;
+    L.a_off = 0;
+    L.g_off = L.a_off + plane_set_bytes(L.a_plane, L.nA * L.nA);
+    L.w_off = L.g_off + plane_set_bytes(L.g_plane, L.nG * L.nG);
+    L.y_off = L.w_off + plane_set_bytes(L.w_plane, L.nG * L.nA);
+    L.bytes = L.y_off + plane_set_bytes(L.w_plane, L.nG * L.nA);
     return L;
 }
+struct LayerPlanes { PlaneSet a, g, w, y; };
+__device__ __forceinline__ LayerPlanes layer_planes(const kfac_precond_item& it, const PlaneLayout& L) {
+    KFAC_AS1 unsigned char* ws = (KFAC_AS1 unsigned char*)as_global((float*)it.ws);
+    LayerPlanes P;
+    P.a.hi = it.Ainv_planes ? (KFAC_AS1 unsigned char*)as_global((float*)it.Ainv_planes) : ws + L.a_off; P.a.plane = L.a_plane;
+    P.g.hi = it.Ginv_planes ? (KFAC_AS1 unsigned char*)as_global((float*)it.Ginv_planes) : ws + L.g_off; P.g.plane = L.g_plane;
+    P.w.hi = ws + L.w_off; P.w.plane = L.w_plane;
+    P.y.hi = ws + L.y_off; P.y.plane = L.w_plane;
+    return P;
+}
+// 128 x 128 blocks the call has to split itself
+static inline __host__ __device__ int split_blocks_A(const kfac_precond_item& it, int nA) { return it.Ainv_planes ? 0 : nA * nA; }
+static inline __host__ __device__ int split_blocks_G(const kfac_precond_item& it, int nG) { return it.Ginv_planes ? 0 : nG * nG; }
 
 __device__ __forceinline__ kfac_precond_item locate_item(const PBatch& b, int wg, int& local) {
     int lo = 0, hi = b.count;
@@ -88,23 +103,24 @@ __device__ __forceinline__ void emit_block(const v4f (&v)[16], KFAC_AS1 unsigned
     for (int p = 0; p < 16; ++p) store_split4_h2(hi, hi + plane, rr + 8 * p, c4, v[p] * sc);
 }
 
-// One 128 x 128 block of Ainv, Ginv or gradW per workgroup.
+// One 128 x 128 block of Ainv, Ginv (unless their planes came with the call) or gradW per workgroup.
 __global__ __launch_bounds__(256) void pre_split_kernel(PBatch b) {
     __shared__ float red[4];
     int local;
     const kfac_precond_item it = locate_item(b, blockIdx.x, local);
     const PlaneLayout L = plane_layout(it.dG, it.dA);
-    KFAC_AS1 unsigned char* ws = (KFAC_AS1 unsigned char*)as_global((float*)it.ws);
+    const LayerPlanes P = layer_planes(it, L);
     const gfloat* X;
     int rows, cols, chunks;
-    size_t hi, plane, sc;
-    if (local < L.nA * L.nA) {
-        X = as_global(it.Ainv); rows = cols = it.dA; chunks = L.nA; hi = L.a_hi; plane = L.a_plane; sc = L.a_sc;
-    } else if ((local -= L.nA * L.nA) < L.nG * L.nG) {
-        X = as_global(it.Ginv); rows = cols = it.dG; chunks = L.nG; hi = L.g_hi; plane = L.g_plane; sc = L.g_sc;
+    PlaneSet set;
+    const int na = split_blocks_A(it, L.nA), ng = split_blocks_G(it, L.nG);
+    if (local < na) {
+        X = as_global(it.Ainv); rows = cols = it.dA; chunks = L.nA; set = P.a;
+    } else if ((local -= na) < ng) {
+        X = as_global(it.Ginv); rows = cols = it.dG; chunks = L.nG; set = P.g;
     } else {
-        local -= L.nG * L.nG;
-        X = as_global(it.gradW); rows = it.dG; cols = it.dA; chunks = L.nA; hi = L.w_hi; plane = L.w_plane; sc = L.w_sc;
+        local -= ng;
+        X = as_global(it.gradW); rows = it.dG; cols = it.dA; chunks = L.nA; set = P.w;
     }
     const int s = local / chunks, c = local - s * chunks;
     const int r0 = s * TM, k0 = c * TM;
@@ -120,7 +136,7 @@ __global__ __launch_bounds__(256) void pre_split_kernel(PBatch b) {
             v[p] = load4_guard(X + (size_t)(row < rows ? row : 0) * cols, row < rows, k0 + c4, cols);
         }
     }
-    emit_block(v, ws + hi + (size_t)local * PRE_SLAB, plane, (gfloat*)(ws + sc) + local, red);
+    emit_block(v, set.hi + (size_t)local * PRE_SLAB, set.plane, set.scales() + local, red);
 }
 
 // phase 1: Yt[dA x dG] = Ainv . gradW^T (written as planes)      phase 2: out[dG x dA] = Ginv . Yt^T
@@ -131,7 +147,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     int local;
     const kfac_precond_item it = locate_item(b, blockIdx.x, local);
     const PlaneLayout L = plane_layout(it.dG, it.dA);
-    KFAC_AS1 unsigned char* ws = (KFAC_AS1 unsigned char*)as_global((float*)it.ws);
+    const LayerPlanes P = layer_planes(it, L);
     // Workgroups go to the 8 XCDs round-robin, each with an L2 of its own.  Inside a block of 8 tile rows, the eight
     // XCDs take one tile row each and walk along it: the tiles that share an A slab (128 rows of the inverse, the
     // large operand when the contraction is long) run on one L2, side by side, instead of on all eight.
@@ -143,14 +159,14 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
     const gfloat *sa, *sb;
     if (phase == 1) {
         run.n = L.nA;
-        run.a_hi = ws + L.a_hi + (size_t)ti * L.nA * PRE_SLAB; run.plane_a = L.a_plane;
-        run.b_hi = ws + L.w_hi + (size_t)tj * L.nA * PRE_SLAB; run.plane_b = L.w_plane;
-        sa = (const gfloat*)(ws + L.a_sc) + ti * L.nA; sb = (const gfloat*)(ws + L.w_sc) + tj * L.nA;
+        run.a_hi = P.a.hi + (size_t)ti * L.nA * PRE_SLAB; run.plane_a = P.a.plane;
+        run.b_hi = P.w.hi + (size_t)tj * L.nA * PRE_SLAB; run.plane_b = P.w.plane;
+        sa = P.a.scales() + ti * L.nA; sb = P.w.scales() + tj * L.nA;
     } else {
         run.n = L.nG;
-        run.a_hi = ws + L.g_hi + (size_t)ti * L.nG * PRE_SLAB; run.plane_a = L.g_plane;
-        run.b_hi = ws + L.y_hi + (size_t)tj * L.nG * PRE_SLAB; run.plane_b = L.y_plane;
-        sa = (const gfloat*)(ws + L.g_sc) + ti * L.nG; sb = (const gfloat*)(ws + L.y_sc) + tj * L.nG;
+        run.a_hi = P.g.hi + (size_t)ti * L.nG * PRE_SLAB; run.plane_a = P.g.plane;
+        run.b_hi = P.y.hi + (size_t)tj * L.nG * PRE_SLAB; run.plane_b = P.y.plane;
+        sa = P.g.scales() + ti * L.nG; sb = P.y.scales() + tj * L.nG;
     }
     run.scale_lds = sc;
     const int t = threadIdx.x;
@@ -196,8 +212,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
             for (int r = 0; r < 16; ++r) m = fmaxf(m, fabsf(acc.c[mb][nb][r]));
     const float sy = panel_scale(block_absmax(m, red));
     const int blkidx = ti * L.nG + tj;
-    if (t == 0) ((gfloat*)(ws + L.y_sc))[blkidx] = sy;
-    KFAC_AS1 unsigned char* yh = ws + L.y_hi + (size_t)blkidx * PRE_SLAB;
+    if (t == 0) P.y.scales()[blkidx] = sy;
+    KFAC_AS1 unsigned char* yh = P.y.hi + (size_t)blkidx * PRE_SLAB;
     constexpr int RLD = TM + 4;
     float* stage = (float*)lds;
     static_assert(64 * RLD * 4 <= PRE_NS * PRE_STAGE, "half a tile fits the ring's memory");
@@ -219,7 +235,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
         for (int p = 0; p < 8; ++p) {
             const int row = rr + 8 * p;
             const v4f x = *(const v4f*)&stage[row * RLD + c4];
-            store_split4_h2(yh, yh + L.y_plane, half * 64 + row, c4, x * sy);
+            store_split4_h2(yh, yh + P.y.plane, half * 64 + row, c4, x * sy);
         }
     }
 }
@@ -237,8 +253,9 @@ static int run_group(const kfac_precond_item* host, const kfac_precond_item* dev
     b.prefix[0] = 0;
     for (int i = 0; i < count; ++i) {
         b.order[i] = (short)i;
-        const int nA = ceil_div(host[first + i].dA, TM), nG = ceil_div(host[first + i].dG, TM);
-        b.prefix[i + 1] = b.prefix[i] + nA * nA + nG * nG + nG * nA;
+        const kfac_precond_item& it = host[first + i];
+        const int nA = ceil_div(it.dA, TM), nG = ceil_div(it.dG, TM);
+        b.prefix[i + 1] = b.prefix[i] + split_blocks_A(it, nA) + split_blocks_G(it, nG) + nG * nA;
     }
     KFAC_LAUNCH(pre_split_kernel, dim3(b.prefix[count]), dim3(256), stream, b);
     for (int phase = 1; phase <= 2; ++phase) {
@@ -263,7 +280,7 @@ static bool item_ok(const kfac_precond_item& it) {
     if (!it.Ginv || !it.Ainv || !it.gradW || !it.out || !it.ws) return false;
     if (it.dG <= 0 || it.dA <= 0 || it.dG > 32768 || it.dA > 32768) return false;
     if (it.out == it.gradW || it.out == it.Ginv || it.out == it.Ainv) return false;
-    if ((uintptr_t)it.ws & 255) return false;
+    if (((uintptr_t)it.ws | (uintptr_t)it.Ginv_planes | (uintptr_t)it.Ainv_planes) & 255) return false;
     return true;
 }
 
@@ -283,6 +300,7 @@ extern "C" int kfac_precondition(const float* Ginv, const float* Ainv, const flo
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < kfac_precondition_workspace_bytes(dG, dA)) return KFAC_ERR_WORKSPACE;
     kfac_precond_item it;
     it.Ginv = Ginv; it.Ainv = Ainv; it.gradW = gradW; it.out = out; it.ws = ws; it.dG = dG; it.dA = dA;
+    it.Ginv_planes = it.Ainv_planes = nullptr;
     return run_group(&it, nullptr, 0, 1, (hipStream_t)stream);
 }
 

@@ -49,6 +49,9 @@ class LayerState:
         self.factor_ws = [kb.alloc_workspace(kb.kfac_factor_workspace_bytes(op, self.desc), device)
                           for op in (kb.KFAC_OP_FACTOR_A, kb.KFAC_OP_FACTOR_G)]
         self.inverse_ws = [kb.alloc_workspace(kb.kfac_inverse_workspace_bytes(d), device) for d in (dA, dG)]
+        # the inverses a second time, as the fp16 piece planes the preconditioning products multiply from (written by the
+        # inversions, kept with the inverses while these are stale)
+        self.A_planes, self.G_planes = (kb.alloc_workspace(kb.kfac_inverse_planes_bytes(d), device) for d in (dA, dG))
         self.pre_ws = kb.alloc_workspace(kb.kfac_precondition_workspace_bytes(dG, dA), device)
 
 
@@ -73,14 +76,16 @@ class _Wave:
                              else kb.FactorBatch(builds, device=device, ws=fws))
         self.pre_batch = kb.PrecondBatch([l.G_inv for l in layers], [l.A_inv for l in layers],
                                          [l.gradW for l in layers], [l.P for l in layers], device=device,
-                                         ws=[l.pre_ws for l in layers])
+                                         ws=[l.pre_ws for l in layers], Ginv_planes=[l.G_planes for l in layers],
+                                         Ainv_planes=[l.A_planes for l in layers])
         self.ema_batch = kb.EmaBatch([t for l in layers for t in (l.A_run, l.G_run)],
                                      [t for l in layers for t in (l.A_new, l.G_new)])
-        src, dst, iws = [], [], []
+        src, dst, iws, planes = [], [], [], []
         for l in layers:
             src += [l.A_run if decay is not None else l.A_new, l.G_run if decay is not None else l.G_new]
             dst += [l.A_inv, l.G_inv]
             iws += l.inverse_ws
+            planes += [l.A_planes, l.G_planes]
         # trace-ratio split of the damping between a layer's factors: computed on the device before the inversions,
         # which read their damping from there
         self.pi_batch = kb.PiBatch(src[0::2], src[1::2], device=device) if pi_split else None
@@ -97,7 +102,7 @@ class _Wave:
             groups[g].append(i)
             load[g] += float(src[i].shape[0]) ** 3
         self.inv_batches = [kb.InverseBatch([src[i] for i in grp], [dst[i] for i in grp], [damping] * len(grp),
-                                            device=device, ws=[iws[i] for i in grp],
+                                            device=device, ws=[iws[i] for i in grp], planes=[planes[i] for i in grp],
                                             dampings_dev=None if lam_dev is None else [lam_dev[i] for i in grp])
                             for grp in groups if grp]
 

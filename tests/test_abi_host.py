@@ -34,8 +34,8 @@ def test_status_strings():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(kb.kfac_layer_desc) == 13 * 4
-    assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8 + 8
-    assert ctypes.sizeof(kb.kfac_precond_item) == 5 * 8 + 8
+    assert ctypes.sizeof(kb.kfac_inverse_item) == 4 * 8 + 8 + 8 + 8
+    assert ctypes.sizeof(kb.kfac_precond_item) == 5 * 8 + 8 + 2 * 8
     assert ctypes.sizeof(kb.kfac_factor_item) == 56 + 4 * 8 + 8 + 16
 
 

@@ -712,6 +712,45 @@ def test_precondition_batched_matches_single_calls():
         np.testing.assert_array_equal(p.cpu().numpy(), gpu_precondition(g, a, w))
 
 
+def test_precondition_from_the_planes_the_inversion_wrote():
+    """kfac_inverse_item.planes -> kfac_precond_item.Ginv_planes / Ainv_planes: the inverse delivered a second time as fp16
+    piece planes, and the preconditioning products multiplying from them, against the oracle and against the same call
+    splitting the fp32 inverses itself.  Sizes: one block, a multiple of the block, ragged, a last block of one row
+    (Eq. 6, Eq. 7)."""
+    shapes = [(64, 65), (256, 577), (130, 129), (128, 1153), (512, 1025), (1, 384)]
+    lam = 0.03
+    rng = np.random.default_rng(21)
+    Sg = [synth.random_spd(g, 40 + i).astype(np.float32) for i, (g, a) in enumerate(shapes)]
+    Sa = [synth.random_spd(a, 60 + i).astype(np.float32) for i, (g, a) in enumerate(shapes)]
+    Ws = [(rng.standard_normal(s) * synth.SIGMA_GRADW).astype(np.float32) for s in shapes]
+    dev = lambda xs: [torch.from_numpy(x).to(DEV) for x in xs]
+    S = dev(Sg) + dev(Sa)
+    Minv = [torch.full_like(x, float("nan")) for x in S]
+    planes = [kb.alloc_workspace(kb.kfac_inverse_planes_bytes(x.shape[0]), DEV) for x in S]
+    for pl in planes:
+        pl.fill_(0x7f)                                    # (fp16 0x7f7f is a huge number: nothing may be left unwritten)
+    inv = kb.InverseBatch(S, Minv, [lam] * len(S), device=DEV, planes=planes)
+    kb.kfac_damped_inverse_batched(inv)
+    torch.cuda.synchronize()
+    assert int(inv.info.abs().max()) == 0
+    n = len(shapes)
+    Gt, At, Wt = Minv[:n], Minv[n:], dev(Ws)
+    P_planes = [torch.full(s, float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+    P_self = [torch.full(s, float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+    kb.kfac_precondition_batched(kb.PrecondBatch(Gt, At, Wt, P_planes, device=DEV, Ginv_planes=planes[:n],
+                                                 Ainv_planes=planes[n:]))
+    kb.kfac_precondition_batched(kb.PrecondBatch(Gt, At, Wt, P_self, device=DEV))
+    torch.cuda.synchronize()
+    for i, (g, a) in enumerate(shapes):
+        gi, ai = Gt[i].cpu().numpy().astype(np.float64), At[i].cpu().numpy().astype(np.float64)
+        assert rel_fro(gi, ko.damped_inverse(Sg[i], lam)) < INV_TOL
+        ref = ko.precondition(gi, Ws[i], ai)
+        got = P_planes[i].cpu().numpy()
+        assert np.isfinite(got).all(), shapes[i]
+        assert rel_fro(got, ref) < 1e-5 and rel_max(got, ref) < 1e-5, (shapes[i], rel_fro(got, ref), rel_max(got, ref))
+        assert rel_fro(got, P_self[i].cpu().numpy()) < 1e-5, shapes[i]
+
+
 def test_precondition_operand_roles():
     """Non-symmetric stand-ins for the inverses would expose a swapped or transposed operand; the ABI takes
     symmetric ones, so use distinct symmetric matrices and a rectangular gradient."""

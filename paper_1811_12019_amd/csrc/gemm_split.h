@@ -176,8 +176,7 @@ __device__ __forceinline__ void tile_mma_nt_split(const gfloat* __restrict__ A, 
 // products h0 h0 + h0 h1 + h1 h0 (exact in the fp32 accumulator) leave a relative error of ~2^-22 per product: on a
 // par with fp32 for a sum of 128 terms, at half the matrix-core work and two thirds of the LDS traffic of three bf16
 // pieces.  fp16 has a narrow exponent range, so every operand panel comes with a power-of-two scale that brings its
-// largest magnitude to about 1 (smaller entries then lose bits only below 2^-24 of the largest, as in fp32 relative
-// to the panel); the caller scales the accumulators to match (exact) and back afterwards.
+// largest magnitude to about 2^8 (smaller entries then lose bits only below 2^-32 of the largest); the caller scales the accumulators to match (exact) and back afterwards.
 typedef _Float16 v2h_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void split4_h2(const v4f& x, uint2 (&piece)[2]) {
@@ -197,15 +196,19 @@ __device__ __forceinline__ void split4_h2(const v4f& x, uint2 (&piece)[2]) {
     }
 }
 
-// Scale (a power of two, as a float) that brings a panel whose largest magnitude is `amax` to at most 1; exponents
-// are kept within +-30 so that products of two scales and their reciprocals stay far from the ends of the fp32 range.
+// Scale (a power of two, as a float) that brings a panel whose largest magnitude is `amax` to at most 2^8: fp16 has
+// seven binades above that before it overflows, and the further up the values sit, the later their low pieces
+// (2^-11 of the value) drop into fp16's subnormal range: entries down to 2^-11 of the largest keep all 22 bits.
+// Exponents are kept within +-30 so that products of two scales and their reciprocals stay far from the ends of the
+// fp32 range.
+constexpr int PANEL_TOP = 8;
 __device__ __forceinline__ float panel_scale(float amax) {
     int e = 0;
     if (amax > 0.f) {
         (void)frexpf(amax, &e);                        // amax = m 2^e, 0.5 <= m < 1
         e = max(-30, min(30, e));
     }
-    return ldexpf(1.0f, -e);
+    return ldexpf(1.0f, PANEL_TOP - e);
 }
 
 // Largest of the 256 threads' values (red: 4 floats of LDS); two barriers.  Must be called by all threads.

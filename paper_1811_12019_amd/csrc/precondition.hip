@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void pre_split_kernel(PBatch b) {
 }
 
 // phase 1: Yt[dA x dG] = Ainv . gradW^T (written as planes)      phase 2: out[dG x dA] = Ginv . Yt^T
-__global__ __launch_bounds__(256) void gemm_nt_kernel(PBatch b, int phase) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) void gemm_nt_kernel(PBatch b, int phase) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[PRE_NS * PRE_STAGE];
     __shared__ float sc[256];
     __shared__ float red[4];

@@ -61,8 +61,10 @@ def kernel_work(net: kstep.KfacNetworkStep):
         "inv_pivot_kernel": ("mfma", PEAK["mfma_f32"], "TFLOP/s", sum(kstep.inverse_first_pivot_flops(d) for d in dims)),
         "inv_panel_kernel": ("mfma", PEAK["mfma_bf16x3"], "TFLOP/s", sum(kstep.inverse_panel_flops(d) for d in dims)),
         "gemm_nt_kernel": ("mfma", PEAK["mfma_f16x2"], "TFLOP/s", sum(kstep.precondition_flops(s.d_G, s.d_A) for s in shapes)),
-        # the operands' piece planes: every element of both inverses and of the gradient read (4 B) and written (2 x 2 B)
-        "pre_split_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(8.0 * (s.d_A * s.d_A + s.d_G * s.d_G + s.d_G * s.d_A) for s in shapes)),
+        # the operands' piece planes: every element read (4 B) and written (2 x 2 B): the gradient by the preconditioning
+        # call, the inverses by the inversion call (kfac_inverse_item.planes)
+        "pre_split_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(8.0 * s.d_G * s.d_A for s in shapes)),
+        "inv_planes_kernel": ("hbm", PEAK["hbm"], "GB/s", sum(8.0 * d * d for d in dims)),
         "factor_generic_kernel": ("alu", PEAK["alu_f32"], "TFLOP/s",
                                   sum(kstep.factor_flops(s.R, s.d_A) for s in shapes if s.C_in % 8 != 0)),
         "factor_dma_kernel<conv>": ("mfma", PEAK["mfma_bf16"], "TFLOP/s", fac_conv),

@@ -36,7 +36,8 @@
 namespace kfac {
 
 constexpr int NB = 128;          // elimination block = tile edge
-constexpr int MAXB = 64;         // matrices per launch group (bounded by the 4 KB of kernel arguments)
+constexpr int MAXB = 64;         // matrices per launch of the kernels that read S (bounded by the 4 KB of kernel arguments)
+constexpr int CMAXB = 112;       // matrices per launch of the sweep's per-step kernels, whose argument block is leaner
 constexpr int UPD_WAVES = 3;     // wavefronts per SIMD the update kernel is compiled for (register budget)
 constexpr int SLD = 132;         // epilogue staging stride (floats) for row-wise float4 access
 constexpr int SLD_T = 129;       // epilogue staging stride when the stage is also read column-wise
@@ -57,6 +58,19 @@ struct Batch {
 };
 
 static_assert(sizeof(Batch) <= 4096, "the batch travels in the kernel arguments");
+
+// The same for the panel and update launches of the sweep, which no longer need the input matrix or the damping: more
+// matrices per launch, i.e. fewer, fuller launches for a batch of many small matrices.
+struct ChainBatch {
+    int count;
+    int prefix[CMAXB + 1];
+    int dim[CMAXB];
+    int step[CMAXB];                  // the elimination step this launch takes for the matrix, or -1: none
+    float* Minv[CMAXB];
+    void* ws[CMAXB];
+    int32_t* info[CMAXB];
+};
+static_assert(sizeof(ChainBatch) <= 4096, "the batch travels in the kernel arguments");
 
 // One matrix of the batch as the kernels see it: pointers typed as global memory.
 struct Item {
@@ -79,11 +93,23 @@ __device__ __forceinline__ Item get_item(const Batch& b, int m) {
     return it;
 }
 
+__device__ __forceinline__ Item get_item(const ChainBatch& b, int m) {
+    Item it;
+    it.S = nullptr;
+    it.Minv = as_global(b.Minv[m]);
+    it.ws = as_global((float*)b.ws[m]);
+    it.info = as_global((int*)b.info[m]);
+    it.dim = b.dim[m];
+    it.damping = 0.f;
+    return it;
+}
+
 // Which matrix workgroup `wg` of a launch belongs to (prefix[m] <= wg < prefix[m + 1]) and its index inside it.
 // Every thread compares one prefix entry and the workgroup counts the matrices that end at or before wg: one vector
 // load and one barrier instead of a binary search of dependent scalar loads (2 us at the start of every workgroup).
 // Must be called by all threads of the workgroup.
-__device__ __forceinline__ void locate(const Batch& b, int wg, int& m, int& local) {
+template <class B>
+__device__ __forceinline__ void locate(const B& b, int wg, int& m, int& local) {
     const int t = threadIdx.x;
     m = __syncthreads_count(t < b.count - 1 && b.prefix[t + 1] <= wg);
     local = wg - b.prefix[m];
@@ -573,7 +599,7 @@ constexpr int PANEL_RLD = NB + 4;          // LDS row stride when the stage is r
 constexpr int PANEL_LDS_FLOATS = NB * PANEL_RLD;
 static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
 
-__global__ __launch_bounds__(256) void inv_panel_kernel(Batch b) {
+__global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
     __shared__ float red[4];
     int m, slab;
@@ -1165,7 +1191,7 @@ __device__ __forceinline__ void chain_tile(const Item& it, const WsView& ws, int
 
 // One launch per step for all matrices of the batch that still have a block `step`; a matrix whose last block this
 // is takes the output-writing paths (LAST), the others update their working copies.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(Batch b) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 8))) void inv_update_kernel(ChainBatch b) {
     __shared__ __attribute__((aligned(1024))) float lds[UNS * USTAGE / 4];
     // Workgroups go to the 8 XCDs round-robin (id % 8) and each XCD has an L2 of its own.  XCD x therefore takes the
     // x-th contiguous eighth of the tile list (matrix by matrix, row-major over the lower triangle): tiles that
@@ -1318,39 +1344,49 @@ static int run_group(const kfac_inverse_item* h, int count, hipStream_t stream) 
     int n_multi = 0;
     while (n_multi < count && nblk_of(h[n_multi].dim) > 1) ++n_multi;
 
-    if (count > n_multi) {
-        // single-block matrices: damp, invert and write in one kernel, straight from S
-        fill_batch(b, h + n_multi, count - n_multi);
+    // single-block matrices: damp, invert and write in one kernel, straight from S
+    for (int first = n_multi; first < count; first += MAXB) {
+        fill_batch(b, h + first, min(MAXB, count - first));
         KFAC_LAUNCH(inv_pivot_kernel, dim3(b.count), dim3(256), stream, b, 0, 1);
     }
     if (n_multi == 0) return KFAC_OK;
-    fill_batch(b, h, n_multi);
-    b.prefix[0] = 0;
-    for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[i].dim);
-    KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n_multi]), dim3(256), stream, b);
+    // damped working copies, then the first pivot blocks (later ones: by the update launches)
+    for (int first = 0; first < n_multi; first += MAXB) {
+        const int n = min(MAXB, n_multi - first);
+        fill_batch(b, h + first, n);
+        b.prefix[0] = 0;
+        for (int i = 0; i < n; ++i) b.prefix[i + 1] = b.prefix[i] + tri_tiles(h[first + i].dim);
+        KFAC_LAUNCH(inv_init_kernel, dim3(b.prefix[n]), dim3(256), stream, b);
+    }
+    for (int first = 0; first < n_multi; first += MAXB) {
+        fill_batch(b, h + first, min(MAXB, n_multi - first));
+        KFAC_LAUNCH(inv_pivot_kernel, dim3(b.count), dim3(256), stream, b, 0, 0);
+    }
     // One panel and one update launch per step of the matrix with the most blocks.  A matrix with fewer blocks takes
     // its steps at evenly spread launches rather than in the first ones: the tile updates of the whole batch are then
     // spread over all launches, each of which lasts at least as long as a pivot workgroup anyway.
-    int done[MAXB] = {};                                // steps taken so far
-    KFAC_LAUNCH(inv_pivot_kernel, dim3(n_multi), dim3(256), stream, b, 0, 0);   // first blocks (later ones: by the update)
+    ChainBatch c;
+    c.count = n_multi;
+    c.prefix[0] = 0;
+    for (int i = 0; i < n_multi; ++i) {
+        c.dim[i] = h[i].dim; c.Minv[i] = h[i].Minv; c.ws[i] = h[i].ws; c.info[i] = h[i].info;
+    }
+    int done[CMAXB] = {};                               // steps taken so far
     for (int l = 0; l < max_steps; ++l) {
-        int panel_wgs = 0, update_wgs = 0;
         for (int i = 0; i < n_multi; ++i) {
             // (a matrix's last two steps touch all of its tiles, the last one on a slow path: matrices with fewer blocks
             // than the largest finish at different launches, none with the largest ones)
             const int n = nblk_of(h[i].dim);
             const int span = n == max_steps ? n : max(n, max_steps - 2 - 2 * (i % 6));
             const bool run = l < span && (int)(((long long)(l + 1) * n) / span) > (int)(((long long)l * n) / span);
-            b.step[i] = run ? done[i] : -1;
+            c.step[i] = run ? done[i] : -1;
         }
-        for (int i = 0; i < n_multi; ++i) b.prefix[i + 1] = b.prefix[i] + (b.step[i] >= 0 ? nblk_of(h[i].dim) : 0);
-        panel_wgs = b.prefix[n_multi];
-        KFAC_LAUNCH(inv_panel_kernel, dim3(panel_wgs), dim3(256), stream, b);
+        for (int i = 0; i < n_multi; ++i) c.prefix[i + 1] = c.prefix[i] + (c.step[i] >= 0 ? nblk_of(h[i].dim) : 0);
+        KFAC_LAUNCH(inv_panel_kernel, dim3(c.prefix[n_multi]), dim3(256), stream, c);
         for (int i = 0; i < n_multi; ++i)
-            b.prefix[i + 1] = b.prefix[i] + (b.step[i] >= 0 ? update_tiles(h[i].dim, b.step[i]) : 0);
-        update_wgs = b.prefix[n_multi];
-        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(n_multi) + xcd_grid(update_wgs)), dim3(256), stream, b);
-        for (int i = 0; i < n_multi; ++i) done[i] += b.step[i] >= 0;
+            c.prefix[i + 1] = c.prefix[i] + (c.step[i] >= 0 ? update_tiles(h[i].dim, c.step[i]) : 0);
+        KFAC_LAUNCH(inv_update_kernel, dim3(xcd_grid(n_multi) + xcd_grid(c.prefix[n_multi])), dim3(256), stream, c);
+        for (int i = 0; i < n_multi; ++i) done[i] += c.step[i] >= 0;
     }
     return KFAC_OK;
 }
@@ -1403,9 +1439,9 @@ extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, 
     }
     // Matrices beyond what one launch's argument block can describe go into further groups.  Dealing them round
     // robin keeps every group's size mix (and hence its step count and load) similar.
-    const int ngroups = (count + MAXB - 1) / MAXB;
+    const int ngroups = (count + CMAXB - 1) / CMAXB;
     for (int g = 0; g < ngroups; ++g) {
-        kfac_inverse_item sel[MAXB];
+        kfac_inverse_item sel[CMAXB];
         int n = 0;
         for (int i = g; i < count; i += ngroups) sel[n++] = items_host[i];
         int rc = run_group(sel, n, (hipStream_t)stream);

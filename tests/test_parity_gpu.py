@@ -617,15 +617,16 @@ def test_damped_inverse_batched_mixed_sizes():
 
 
 def test_damped_inverse_batched_more_matrices_than_one_launch_group():
-    """70 small matrices of mixed size in one call: more than one launch's argument block describes, so the call
-    deals them into groups; every one against the oracle, and bit for bit against the single call."""
-    dims = [1 + (37 * i) % 300 for i in range(66)] + [385, 257, 129, 128]
+    """150 small matrices of mixed size in one call: more than one launch's argument block describes (64 for the kernels
+    that read the input, 112 for the sweep's per-step launches), so the call deals them into groups and sub-batches;
+    every one against the oracle, and bit for bit against the single call."""
+    dims = [1 + (37 * i) % 300 for i in range(146)] + [385, 257, 129, 128]
     Ss = [synth.random_spd(d, seed=100 + i, n_zero=d // 5) for i, d in enumerate(dims)]
     lams = [0.02 + 0.001 * i for i in range(len(dims))]
     St = [torch.from_numpy(s).to(DEV) for s in Ss]
     Mt = [torch.full((d, d), float("nan"), dtype=torch.float32, device=DEV) for d in dims]
     batch = kb.InverseBatch(St, Mt, lams, device=DEV)
-    assert batch.count == 70
+    assert batch.count == 150
     kb.kfac_damped_inverse_batched(batch)
     torch.cuda.synchronize()
     assert batch.info.cpu().tolist() == [0] * len(dims)

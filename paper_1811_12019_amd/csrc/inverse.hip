@@ -539,6 +539,7 @@ __device__ __forceinline__ void pivot_write(const v16f (&acc)[2][2], float* __re
 // from_S: single-block matrices: read S + lambda I and write the caller's output directly.
 __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int from_S) {
     __shared__ __attribute__((aligned(16))) float lds[PIV_LDS_FLOATS];
+    __builtin_amdgcn_s_setprio(3);
     const int m = blockIdx.x;
     const Item it = get_item(b, m);
     const int d = it.dim;
@@ -602,6 +603,7 @@ static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= spl
 __global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
     __shared__ float red[4];
+    __builtin_amdgcn_s_setprio(3);                       // a link of the chain: ahead of whatever shares its SIMDs
     int m, slab;
     locate(b, blockIdx.x, m, slab);
     const Item it = get_item(b, m);
@@ -1201,6 +1203,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     const int npiv = (b.count + 7) & ~7;
     if ((int)blockIdx.x < npiv) {
         if ((int)blockIdx.x >= b.count) return;
+        __builtin_amdgcn_s_setprio(3);                   // the chain's longest link: ahead of whatever shares its SIMDs
         const Item it = get_item(b, blockIdx.x);
         const int step = b.step[blockIdx.x];
         if (step >= 0 && nblk_of(it.dim) > step + 1) upd_next_pivot(it, step, lds);
@@ -1230,6 +1233,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
         return;
     }
     if (pl.kind == PLAN_CHAIN) {
+        __builtin_amdgcn_s_setprio(2);                   // the next panel waits for these; lag tiles do not hurry
         chain_decode(nblk, step + 1, pl.d_begin, tile, I, J);
         if (I != J) chain_tile(it, ws, I, J, step, lds);
         else group_tile(it, ws, I, J, pl.g, pl.g.j < pl.g.m - 1, lds);   // kept up to date step by step inside a group

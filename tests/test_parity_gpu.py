@@ -741,8 +741,11 @@ def test_precondition_from_the_planes_the_inversion_wrote():
     kb.kfac_precondition_batched(kb.PrecondBatch(Gt, At, Wt, P_planes, device=DEV, Ginv_planes=planes[:n],
                                                  Ainv_planes=planes[n:]))
     kb.kfac_precondition_batched(kb.PrecondBatch(Gt, At, Wt, P_self, device=DEV))
+    P_mixed = [torch.full(s, float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+    kb.kfac_precondition_batched(kb.PrecondBatch(Gt, At, Wt, P_mixed, device=DEV, Ainv_planes=planes[n:]))   # G split by the call
     torch.cuda.synchronize()
     for i, (g, a) in enumerate(shapes):
+        assert rel_fro(P_mixed[i].cpu().numpy(), P_planes[i].cpu().numpy()) < 1e-5, shapes[i]
         gi, ai = Gt[i].cpu().numpy().astype(np.float64), At[i].cpu().numpy().astype(np.float64)
         assert rel_fro(gi, ko.damped_inverse(Sg[i], lam)) < INV_TOL
         ref = ko.precondition(gi, Ws[i], ai)

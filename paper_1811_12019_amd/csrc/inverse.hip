@@ -343,14 +343,14 @@ __device__ __forceinline__ int invert16_wave(const float* __restrict__ D16, int 
         for (int q = 0; q < 4; ++q)
             vc[q] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (4 * (4 * g + q)), __float_as_int(vi)));
         const float wi = vi * ip;
+        // (selects, not branches: the pivot row's lanes would otherwise run a path of their own after everybody else's)
+        const bool prow = i == s, pcol = g == (s >> 2);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) E[q] = fmaf(-wi, vc[q], E[q]);
-        if (g == (s >> 2)) E[s & 3] = wi;
-        if (i == s) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) E[q] = vc[q] * ip;
-            if (g == (s >> 2)) E[s & 3] = -ip;
+        for (int q = 0; q < 4; ++q) {
+            const float upd = fmaf(-wi, vc[q], E[q]), piv = vc[q] * ip;
+            E[q] = prow ? piv : upd;
         }
+        E[s & 3] = pcol ? (prow ? -ip : wi) : E[s & 3];
     }
     // E = -P16 up to rounding asymmetry: publish, then re-read the lower triangle so that P16 is exactly symmetric
 #pragma unroll

@@ -395,6 +395,57 @@ __device__ __forceinline__ void pivot_fill(v16f (&acc)[2][2], const float* __res
     __syncthreads();
 }
 
+// D (accumulator layout) holds a symmetric block's lower triangle; the rest is filled in from it, bordered by the
+// identity beyond nb.  Three 64 x 64 transposes through LDS (3 x 4096 floats): the quadrant below the diagonal goes,
+// transposed, to the wavefront that owns the quadrant above it, and each diagonal quadrant to itself.  Element (a, b)
+// of a quadrant is kept at b * 64 + (a ^ b): writes (lanes along b) and reads (lanes along a) both touch 32 different
+// banks.  Ends with a barrier: lds may be overwritten afterwards.
+__device__ __forceinline__ void pivot_symmetrize(v16f (&acc)[2][2], float* __restrict__ lds, int nb) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, h = lane >> 5;
+    // writers: wavefronts (0,0), (1,0), (1,1) -> squares 0, 1, 2
+    if (!(wm == 0 && wn == 1)) {
+        float* sq = lds + (wm + wn) * 4096;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int a = mb * 32 + (r >> 2) * 8 + h * 4 + (r & 3), b = nbk * 32 + lm;
+                    sq[b * 64 + (a ^ b)] = acc[mb][nbk][r];
+                }
+    }
+    __syncthreads();
+    // readers: target (a, b) of a quadrant takes source (b, a) of square (0,0) -> 0, (0,1) -> 1, (1,1) -> 2
+    if (!(wm == 1 && wn == 0)) {
+        const float* sq = lds + (wm + wn) * 4096;
+        const bool whole = wm != wn;                     // the quadrant above the diagonal: every element
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int a = mb * 32 + (r >> 2) * 8 + h * 4 + (r & 3), b = nbk * 32 + lm;
+                    const float v = sq[a * 64 + (b ^ a)];
+                    acc[mb][nbk][r] = (whole || a < b) ? v : acc[mb][nbk][r];
+                }
+    }
+    if (nb < NB) {                                       // (uniform) ragged block: identity beyond nb
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
+                    if (!(row < nb && col < nb)) acc[mb][nbk][r] = row == col ? 1.f : 0.f;
+                }
+    }
+    __syncthreads();
+}
+
 // The symmetric sweep of D in 16-wide sub-blocks (see above); lds: PIV_LDS_FLOATS floats.  Returns (to every thread)
 // the 1-based index inside the block of the first non-positive pivot, or 0.  Ends with a barrier.
 __device__ __forceinline__ int pivot_sweep(v16f (&acc)[2][2], int nb, float* __restrict__ lds) {
@@ -1053,18 +1104,8 @@ __device__ __forceinline__ void upd_next_pivot(const Item& it, int step, float* 
     const PanelRun pl = panel_run(ws, step, 1, kn, kn);
     upd_regular_mid_split<false>(c, o, pl, (unsigned char*)lds, acc);
     __syncthreads();                                     // the product's LDS stages are free
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
-                if (row >= col && row < nb) lds[tri_at(row, col)] = acc.c[mb][nbk][r];
-            }
-    __syncthreads();
-    pivot_fill<true>(acc.c, lds, nb);
+    const int t = threadIdx.x;
+    pivot_symmetrize(acc.c, lds, nb);
     const int f = pivot_sweep(acc.c, nb, lds);
     if (t == 0 && it.info && f != 0) atomicCAS((int*)it.info, 0, k0 + f);
     pivot_write(acc.c, lds, it, ws, k0, nb, k0 + NB >= d, false);

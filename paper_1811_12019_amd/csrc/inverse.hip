@@ -555,6 +555,22 @@ __device__ __forceinline__ void pivot_write(const v16f (&acc)[2][2], float* __re
                                             const WsView& ws, int k0, int nb, bool last, bool from_S) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int d = it.dim;
+    if (!last && !from_S && nb == NB) {
+        // A full block inside the sweep (the look-ahead pivot's usual case): the registers hold the whole symmetric block,
+        // and a half-wave's 32 lanes hold 32 consecutive floats of a row, so it goes out as it is.
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = acc_row(wm, mb, r, lane), col = acc_col(wn, nbk, lane);
+                    const float x = acc[mb][nbk][r];
+                    ws.W[(size_t)(k0 + row) * ws.ldw + k0 + col] = x;
+                    ws.P[row * NB + col] = -x;
+                }
+        return;
+    }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll

@@ -456,7 +456,6 @@ __device__ __forceinline__ int pivot_sweep(v16f (&acc)[2][2], int nb, float* __r
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, h = lane >> 5;
     if (t == 0) *bad = 0;
-    const int trow = t >> 1, tc0 = (t & 1) * 8;      // T16: thread -> one row, 8 of the 16 columns
 #pragma unroll
     for (int jb = 0; jb < NB / PSB; ++jb) {
         const int j0 = jb * PSB;
@@ -480,30 +479,26 @@ __device__ __forceinline__ int pivot_sweep(v16f (&acc)[2][2], int nb, float* __r
             if (f != 0 && lane == 0 && *bad == 0) *bad = j0 + f;
         }
         __syncthreads();
-        // 3. T16 = U16 . P16, rows of the sub-block replaced by -P16
+        // 3. T16 = U16 . P16 on the matrix cores (v_mfma_f32_16x16x4_f32: lane l supplies A[l % 16][l / 16] and
+        //    B[l / 16][l % 16] and receives C[4 (l / 16) + i][l % 16], i < 4); a wavefront takes 32 of the 128 rows.
+        //    The rows of the sub-block itself are replaced by -P16.
         {
-            float tv[8] = {};
-            const v4f* up = (const v4f*)&Us[trow * PLD];
+            const int l16 = lane & 15, lq = lane >> 4;
 #pragma unroll
-            for (int k4 = 0; k4 < 4; ++k4) {
-                const v4f u = up[k4];
+            for (int rbi = 0; rbi < 2; ++rbi) {
+                const int rb0 = (2 * wave + rbi) * PSB;          // first row of this 16-row block
+                v4f c4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const v4f p0 = *(const v4f*)&Ps[(4 * k4 + kk) * PLD + tc0];
-                    const v4f p1 = *(const v4f*)&Ps[(4 * k4 + kk) * PLD + tc0 + 4];
+                for (int kk = 0; kk < 4; ++kk)
+                    c4 = __builtin_amdgcn_mfma_f32_16x16x4f32(Us[(rb0 + l16) * PLD + 4 * kk + lq], Ps[(4 * kk + lq) * PLD + l16],
+                                                               c4, 0, 0, 0);
+                const bool own = rb0 == j0;                      // (uniform)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        tv[c] = fmaf(u[kk], p0[c], tv[c]);
-                        tv[4 + c] = fmaf(u[kk], p1[c], tv[4 + c]);
-                    }
+                for (int i2 = 0; i2 < 4; ++i2) {
+                    const int rl = 4 * lq + i2;
+                    Ts[(rb0 + rl) * PLD + l16] = own ? -Ps[rl * PLD + l16] : c4[i2];
                 }
             }
-            if (trow >= j0 && trow < j0 + PSB) {
-#pragma unroll
-                for (int c = 0; c < 8; ++c) tv[c] = -Ps[(trow - j0) * PLD + tc0 + c];
-            }
-            *(v4f*)&Ts[trow * PLD + tc0] = v4f{tv[0], tv[1], tv[2], tv[3]};
-            *(v4f*)&Ts[trow * PLD + tc0 + 4] = v4f{tv[4], tv[5], tv[6], tv[7]};
         }
         __syncthreads();
         // 4. D -= T16 . U16^T  (lane (lm, h) takes k = 8s + 4h .. +3 of both operands), then the fix-ups

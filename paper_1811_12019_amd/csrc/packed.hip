@@ -11,10 +11,7 @@
 
 namespace kfac {
 
-#ifndef PK_TILE
-#define PK_TILE 128
-#endif
-constexpr int PK_T = PK_TILE;         // tile edge
+constexpr int PK_T = 128;             // tile edge
 constexpr int PK_MAX = 128;           // matrices per launch (keeps the argument block under 4 KB)
 
 struct PackBatch {
@@ -103,9 +100,7 @@ __global__ __launch_bounds__(256) void pack_upper_kernel(PackBatch b) {
 constexpr int PK_TPR = PK_T / 4;            // threads per tile row
 constexpr int PK_RPP = 256 / PK_TPR;        // tile rows per pass
 constexpr int PK_NP = PK_T / PK_RPP;        // passes
-#ifndef PK_GROUP
-#define PK_GROUP 8                          // passes whose loads are in flight together
-#endif
+constexpr int PK_GROUP = 8;                 // passes whose loads are in flight together
 __global__ __launch_bounds__(256) void ema_packed_kernel(PackBatch b, float decay, float one_minus) {
     __shared__ float tile[PK_T][PK_T + 1];
     int m, I, J;

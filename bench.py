@@ -76,6 +76,19 @@ def kernel_work(net: kstep.KfacNetworkStep):
     return w
 
 
+def factor_shape_roofline_ms(layers):
+    """Ideal time of the factor stage: per factor the larger of its algorithmic flops at the bf16 matrix-core peak and
+    its algorithmic bytes at the HBM peak (16-bit input tensor read once, not the unfolded matrix; the running average
+    read and written, 8 bytes per element), summed over both factors of every layer."""
+    total = 0.0
+    for s in layers:
+        for d, in_elems in ((s.d_A, s.N * s.C_in * s.H * s.W), (s.d_G, s.R * s.d_G)):
+            t_mfma = kstep.factor_flops(s.R, d) / (PEAK["mfma_bf16"] * 1e12)
+            t_hbm = (2.0 * in_elems + 8.0 * d * d) / (PEAK["hbm"] * 1e9)
+            total += max(t_mfma, t_hbm)
+    return total * 1e3
+
+
 def measured_traffic(kernel: str, batch: int):
     """HBM bytes per launch of `kernel` as rocprofv3's FETCH_SIZE + WRITE_SIZE counters measured them on this
     workload (scaled by a copy kernel of known size); the figure is kept with the profile summaries.  None when no
@@ -356,6 +369,7 @@ def main():
                 "avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"]}
 
     fac_flops = sum(kstep.factor_flops(s.R, s.d_A) + kstep.factor_flops(s.R, s.d_G) for s in layers)
+    fac_ideal_ms = factor_shape_roofline_ms(layers)
     out = {
         "metric": "ResNet-50 K-FAC step ms/GPU @ batch 32; factor TFLOP/s & % MFMA peak",
         "value": round(ms, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -369,6 +383,10 @@ def main():
         "schedule": f"{len(net.waves)} waves" if net.pipelined and net.waves else "stage by stage",
         "factor_tflops": round(fac_flops / (stages["factors"] * 1e-3) / 1e12, 2),
         "factor_frac_of_bf16_mfma_peak": round(fac_flops / (stages["factors"] * 1e-3) / 1e12 / PEAK["mfma_bf16"], 4),
+        # many factors are bandwidth- rather than matrix-core-bound (narrow ones over many rows): the sum over all 108
+        # of the larger of their two ideal times, against the stage
+        "factor_shape_roofline_ms": round(fac_ideal_ms, 4),
+        "factor_frac_of_shape_roofline": round(fac_ideal_ms / stages["factors"], 4),
         "roofline": roofline,
         "kernels": per_kernel,
     }

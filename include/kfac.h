@@ -23,7 +23,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
  *     work; they do not synchronise.  Buffers must stay valid until the stream has drained.
  *   - Return value: KFAC_OK or a negative kfac_status.  Argument errors are detected on the host
- *     before anything is launched.  Numerical failure of an inversion (matrix not positive
+ *     before anything is launched; a batched call with count = 0 returns KFAC_OK and launches
+ *     nothing, a negative count is an argument error.  Numerical failure of an inversion (matrix not positive
  *     definite) is reported through the device-side `info` word, LAPACK potrf style.
  *   - Thread safety: calls from different host threads, on different streams, with disjoint buffers
  *     may run concurrently (the measurement aid takes a lock of its own when it is on).

@@ -537,6 +537,7 @@ extern "C" int kfac_factor_G(const kfac_layer_desc* desc, const void* gout, floa
 
 extern "C" int kfac_factor_batched(const kfac_factor_item* items_host, const kfac_factor_item* items_dev, int32_t count,
                                    void* stream) {
-    if (!items_host || !items_dev || count <= 0) return KFAC_ERR_INVALID_ARG;
+    if (count == 0) return KFAC_OK;                       // nothing to do, no launch
+    if (!items_host || !items_dev || count < 0) return KFAC_ERR_INVALID_ARG;
     return run_factor_items(items_host, items_dev, count, (hipStream_t)stream);
 }

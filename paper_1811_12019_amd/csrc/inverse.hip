@@ -1488,7 +1488,8 @@ extern "C" int kfac_damped_inverse(const float* S, int32_t dim, float damping, f
 }
 
 extern "C" int kfac_damped_inverse_batched(const kfac_inverse_item* items_host, int32_t count, void* stream) {
-    if (!items_host || count <= 0) return KFAC_ERR_INVALID_ARG;
+    if (count == 0) return KFAC_OK;                       // nothing to do, no launch
+    if (!items_host || count < 0) return KFAC_ERR_INVALID_ARG;
     for (int i = 0; i < count; ++i) {
         if (!item_ok(items_host[i])) return KFAC_ERR_INVALID_ARG;
         if (i > 0 && items_host[i].dim > items_host[i - 1].dim) return KFAC_ERR_INVALID_ARG;   // sorted, largest first

@@ -306,7 +306,8 @@ extern "C" int kfac_precondition(const float* Ginv, const float* Ainv, const flo
 
 extern "C" int kfac_precondition_batched(const kfac_precond_item* items_host, const kfac_precond_item* items_dev,
                                          int32_t count, void* stream) {
-    if (!items_host || !items_dev || count <= 0) return KFAC_ERR_INVALID_ARG;
+    if (count == 0) return KFAC_OK;                       // nothing to do, no launch
+    if (!items_host || !items_dev || count < 0) return KFAC_ERR_INVALID_ARG;
     for (int i = 0; i < count; ++i)
         if (!item_ok(items_host[i])) return KFAC_ERR_INVALID_ARG;
     for (int first = 0; first < count; first += PMAXB) {

@@ -78,6 +78,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     fit[0] = kb.kfac_factor_item(big, 0x1000, 0x2000, None, 0, 0.0, 9, None, 0.0, 0)                          # unknown op
     assert lib.kfac_factor_batched(fit, fake, 1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_factor_batched(fit, None, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_factor_batched(fit, fake, 0, None) == kb.KFAC_OK                    # nothing to do, no launch
+    assert lib.kfac_factor_batched(fit, fake, -1, None) == kb.KFAC_ERR_INVALID_ARG
 
     assert lib.kfac_ema(None, fake, 4, 0.95, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_ema(fake, fake, 4, 0.95, None) == kb.KFAC_ERR_INVALID_ARG          # overlap
@@ -138,13 +140,16 @@ def test_bad_arguments_are_rejected_on_the_host():
     items[0] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 64, 0.1, None)
     items[1] = kb.kfac_inverse_item(0x1000, 0x90000, 0x200000, None, 300, 0.1, None)       # not sorted largest-first
     assert lib.kfac_damped_inverse_batched(items, 2, None) == kb.KFAC_ERR_INVALID_ARG
-    assert lib.kfac_damped_inverse_batched(items, 0, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_damped_inverse_batched(items, 0, None) == kb.KFAC_OK                # nothing to do, no launch
+    assert lib.kfac_damped_inverse_batched(items, -1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_damped_inverse_batched(None, 1, None) == kb.KFAC_ERR_INVALID_ARG
 
     pit = (kb.kfac_precond_item * 1)()
     pit[0] = kb.kfac_precond_item(0x1000, 0x2000, 0x3000, 0x3000, 0x4000, 4, 5)      # out aliases gradW
     assert lib.kfac_precondition_batched(pit, fake, 1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_precondition_batched(pit, None, 1, None) == kb.KFAC_ERR_INVALID_ARG
+    assert lib.kfac_precondition_batched(pit, fake, 0, None) == kb.KFAC_OK              # nothing to do, no launch
+    assert lib.kfac_precondition_batched(pit, fake, -1, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, None, fake, 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, ctypes.c_void_p(0x9000), None, 0, None) == kb.KFAC_ERR_WORKSPACE
     assert lib.kfac_precondition(fake, fake, fake, 4, 5, fake, ctypes.c_void_p(0x9000), 1 << 20, None) == kb.KFAC_ERR_INVALID_ARG

@@ -255,7 +255,7 @@ __device__ __forceinline__ void store_split4_h2(KFAC_AS1 unsigned char* hi, KFAC
 }
 
 // The rank-128 products of a tile.  The operands of consecutive products sit in consecutive buffers of a ring of `nbuf`
-// (a power of two) equally laid out buffers `stride` bytes apart: product q reads buffer (first + q) mod nbuf, the
+// equally laid out buffers `stride` bytes apart: product q reads buffer (first + q) mod nbuf, the
 // high pieces of its A slab at a_hi + buffer * stride, the low pieces `plane` bytes further, and likewise b_hi;
 // scale[q] = sa * sb is what the product of the stored pieces is scaled by.
 template <int MAXN>
@@ -293,7 +293,8 @@ __device__ __forceinline__ float tile_mma_presplit(const SplitRun<MAXN>& p, unsi
     auto issue = [&](int s, int buf) {
         const int sc = s < nst ? s : nst - 1;          // past the end: re-read the last slice (never consumed)
         const int q = sc / NSL, ks = sc - q * NSL;
-        const size_t boff = (size_t)((p.first + q) & (p.nbuf - 1)) * p.stride;
+        const int bq = p.first + q;                    // (first < nbuf, q < nbuf)
+        const size_t boff = (size_t)(bq >= p.nbuf ? bq - p.nbuf : bq) * p.stride;
         const KFAC_AS1 unsigned char* pa = p.a_hi + boff;
         const KFAC_AS1 unsigned char* pb = p.b_hi + boff;
         const KFAC_AS1 unsigned char* src[4] = {pa, pa + p.plane, pb, pb + p.plane};

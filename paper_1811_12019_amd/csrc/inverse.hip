@@ -164,6 +164,8 @@ static inline __host__ __device__ Group group_of(int dim, int step) {
 //         kept up to date step by step so that a look-ahead pivot never owes more than one product; in a group's last
 //         step these are the diagonal tiles of the next group's blocks and of the first block after those, which see
 //         the whole group.
+//     In a group's last step the off-diagonal tiles of the next group's other block columns / rows also see the whole
+//     group ("early" tiles: not needed by the next step, but their chain visits then owe only their own group's steps).
 //     Every other tile owes the group's steps: the rest of the matrix is dealt, as lag tiles, to the next group's
 //     chain launches (all but its last), where it runs beside the pivot workgroups that set those launches' duration.
 //   * Whole: the last step of a group that is not followed by a group of two or more steps; all tiles of the triangle
@@ -177,6 +179,8 @@ struct Plan {
     int chain;           // number of chain tiles
     int lag;             // number of lag tiles in this launch
     int lag_off;         // index of the first one in the lag list
+    int early;           // number of early tiles (a group's last step; no lag tiles then): see plan_of
+    int next_m;          // size of the next group (early tiles)
 };
 constexpr int PLAN_CHAIN = 0, PLAN_WHOLE = 2, PLAN_LAST = 3;
 
@@ -185,6 +189,7 @@ static inline __host__ __device__ Plan plan_of(int dim, int step) {
     Plan p;
     p.g = group_of(dim, step);
     p.lag = p.lag_off = 0;
+    p.early = p.next_m = 0;
     p.d_begin = p.d_end = 0;
     if (p.g.m == 0) { p.kind = PLAN_LAST; p.chain = n * (n + 1) / 2; return p; }
     const int E = p.g.g0 + p.g.m;
@@ -205,6 +210,12 @@ static inline __host__ __device__ Plan plan_of(int dim, int step) {
         p.kind = PLAN_CHAIN;
         p.d_begin = E + 1; p.d_end = E + next.m + 1;
         p.chain = n - 1 + p.d_end - p.d_begin;
+        // Early tiles: the off-diagonal tiles of the next group's other block columns / rows c = E + 1 .. E + next.m - 1
+        // (row part J < E, column part I > c) receive this group's steps now, beside the chain tiles and off the chain,
+        // so that their own chain visits inside the next group owe only that group's steps (1 .. 3 products instead of
+        // 5 .. 7 on the chain's critical path).
+        p.next_m = next.m;
+        for (int c = E + 1; c < E + next.m; ++c) p.early += E + n - 1 - c;
     } else {
         p.kind = PLAN_WHOLE;
         p.chain = n * (n + 1) / 2;
@@ -213,7 +224,7 @@ static inline __host__ __device__ Plan plan_of(int dim, int step) {
 }
 static inline __host__ __device__ int update_tiles(int dim, int step) {
     const Plan p = plan_of(dim, step);
-    return p.chain + p.lag;
+    return p.chain + p.lag + p.early;
 }
 // Tile index of a chain list -> (I, J): block row c = step + 1 left of the diagonal, block column c below it, then
 // the diagonal tiles d_begin ..
@@ -221,6 +232,19 @@ __device__ __forceinline__ void chain_decode(int n, int c, int d_begin, int t, i
     if (t < c) { I = c; J = t; }
     else if (t < n - 1) { I = t + 1; J = c; }
     else { I = J = d_begin + (t - (n - 1)); }
+}
+// index in the early list of a launch (E: first block of the next group, nm its size) -> (I, J)
+__device__ __forceinline__ void early_decode(int n, int E, int nm, int t, int& I, int& J) {
+    for (int c = E + 1; c < E + nm; ++c) {
+        const int cnt = E + n - 1 - c;
+        if (t < cnt) {
+            if (t < E) { I = c; J = t; }
+            else { I = c + 1 + (t - E); J = c; }
+            return;
+        }
+        t -= cnt;
+    }
+    I = J = 0;                                           // (not reached)
 }
 // index in the lag list of a group [E, E + m) -> (I, J): the lower triangle over the blocks outside the group
 __device__ __forceinline__ void lag_decode(int n, int E, int m, int t, int& I, int& J) {
@@ -1007,7 +1031,7 @@ struct OldSrc {
 // and the result is stored from the registers: nothing is staged in LDS.
 // STORE = false: the new values stay in acc (valid where the tile has rows and columns;
 // the quadrant above the diagonal of a diagonal tile is not computed) and nothing is written.
-constexpr int MAXRUN = 2 * GM - 1;       // a tile can owe the whole group before and all but one step of its own group
+constexpr int MAXRUN = GM;               // a tile owes at most one whole group (the group before, or its own so far)
 typedef SplitRun<MAXRUN> PanelRun;
 
 // The products of tile (I, J) with the panels of the n consecutive steps first_step .. first_step + n - 1 (buffer =
@@ -1215,9 +1239,11 @@ __device__ __forceinline__ void group_tile(const Item& it, const WsView& ws, int
 //   other == k              it becomes part of panel k: T_I of this step (block column k)
 //   lo <= other < k         block column `other` was eliminated at a step inside the window the tile can owe: the tile
 //                           then became T_I of that step (not written to the working copy), and owes the steps after it
-//   otherwise               its value in the working copy is up to date through step lo - 1, lo the first step of the
-//                           group before c's own (the bulk update of that group ran while c's group had begun and
-//                           skipped the tiles with an index inside it), and it owes lo .. k.
+//   otherwise               its value in the working copy is up to date through step lo - 1 and it owes lo .. k.  For the
+//                           first block of a group, lo is the first step of the group before (whose bulk update ran
+//                           while that group was under way and skipped the tiles with an index inside it); for the other
+//                           blocks of a group it is the group's own first step (the last launch of the group before
+//                           brought their tiles up to date: the early tiles of plan_of).
 __device__ __forceinline__ void chain_tile(const Item& it, const WsView& ws, int I, int J, int k, float* __restrict__ lds) {
     const int c1 = k + 1;
     UpdCtx c;
@@ -1231,7 +1257,7 @@ __device__ __forceinline__ void chain_tile(const Item& it, const WsView& ws, int
         upd_panel<false>(c, true, lds);
         return;
     }
-    const int lo = max(0, c1 / GM * GM - GM);
+    const int lo = c1 % GM == 0 ? max(0, c1 - GM) : c1 / GM * GM;
     OldSrc o = {ws.W + (size_t)c.i0 * ws.ldw + c.j0, ws.ldw, 1};
     int first = lo;
     if (I == c1 && J >= lo) {                            // (J < k here)
@@ -1274,6 +1300,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(UPD_WAVES, 
     const Plan pl = plan_of(it.dim, step);
     const WsView ws = ws_view(it.ws, it.dim);
     int I, J;
+    if (tile >= pl.chain && pl.early > 0) {
+        // early tile: this group's steps, all of them (the launch is the group's last)
+        early_decode(nblk, pl.g.g0 + pl.g.m, pl.next_m, tile - pl.chain, I, J);
+        group_tile(it, ws, I, J, pl.g, false, lds);
+        return;
+    }
     if (tile >= pl.chain) {
         // lag tile: the whole update of the previous group (steps g0 - GM .. g0 - 1, all GM of them)
         lag_decode(nblk, pl.g.g0, pl.g.m, pl.lag_off + tile - pl.chain, I, J);

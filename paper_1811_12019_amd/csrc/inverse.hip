@@ -681,10 +681,14 @@ __global__ __launch_bounds__(256) void inv_pivot_kernel(Batch b, int step, int f
 // Full pivot block (every step but a matrix's last): the slab is first copied to U (through an LDS transpose for the
 // slabs above the pivot), all 64 KB in flight at once, and the product then runs on the bf16 matrix cores with both
 // operands split three ways, reading the copy.  Ragged pivot block: fp32 matrix cores, operands guarded.
+// The transpose and the way out of T pass through LDS 64 rows at a time, so that the workgroup needs no more LDS than
+// the product (48 KB): a panel workgroup then fits into the room one finished update (or factor) workgroup leaves on
+// a CU.  With a full 128-row stage (66 KB) it had to wait until two of them had finished on the same CU, and the
+// panel launches, links of the chain, lasted 47 us instead of 21 us while other streams kept the CUs full.
 constexpr int PANEL_TLD = NB + 1;          // LDS row stride of the transpose stage
 constexpr int PANEL_RLD = NB + 4;          // LDS row stride when the stage is read back four columns at a time
-constexpr int PANEL_LDS_FLOATS = NB * PANEL_RLD;
-static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS * 4 >= split_lds_bytes<3>(), "one buffer serves all uses");
+constexpr int PANEL_LDS_FLOATS = split_lds_bytes<3>() / 4;
+static_assert(PANEL_LDS_FLOATS >= GEMM_LDS_FLOATS && PANEL_LDS_FLOATS >= (NB / 2) * PANEL_RLD, "one buffer serves all uses");
 
 __global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
     __shared__ __attribute__((aligned(16))) float lds[PANEL_LDS_FLOATS];
@@ -724,16 +728,6 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
 #pragma unroll
             for (int p = 0; p < 16; ++p)
                 v[p] = *(const KFAC_AS1 v4f*)&ws.W[(size_t)(k0 + rr + 8 * p) * ws.ldw + r0 + c4];
-#pragma unroll
-            for (int p = 0; p < 16; ++p)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) lds[(c4 + i) * PANEL_TLD + rr + 8 * p] = v[p][i];
-            __syncthreads();
-#pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                const float* src = &lds[(rr + 8 * p) * PANEL_TLD + c4];
-                *(KFAC_AS1 v4f*)&Uc[(size_t)(rr + 8 * p) * NB + c4] = v4f{src[0], src[1], src[2], src[3]};
-            }
         }
         float um = 0.f;                        // the slab's scale for the update's fp16 pieces
 #pragma unroll
@@ -743,16 +737,32 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
         um = block_absmax(um, red);
         const float su = panel_scale(um);
         if (t == 0) ws.scaleU(q, slab) = su;
-        {   // the slab's scaled fp16 pieces (thread: columns c4 .. c4 + 3 of rows rr + 8 p, as in the copy above)
-            KFAC_AS1 unsigned char* uh = ws.UH(q) + (size_t)slab * PRE_SLAB;
+        // the copy (slabs above the pivot) and the slab's scaled fp16 pieces
+        KFAC_AS1 unsigned char* uh = ws.UH(q) + (size_t)slab * PRE_SLAB;
+        if (slab > step) {
 #pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                v4f x = v[p];
-                if (slab < step) {
-                    const float* src = &lds[(rr + 8 * p) * PANEL_TLD + c4];
-                    x = v4f{src[0], src[1], src[2], src[3]};
+            for (int p = 0; p < 16; ++p) store_split4_h2(uh, uh + ws.plane, rr + 8 * p, c4, v[p] * su);
+        } else {
+            // transposed through LDS, 64 rows of the slab at a time: the threads holding columns c4 .. c4 + 3 of that
+            // half write them, then every thread reads four consecutive elements of eight rows
+#pragma unroll 1
+            for (int half = 0; half < 2; ++half) {
+                if (half == 1) __syncthreads();
+                if ((c4 >> 6) == half) {
+#pragma unroll
+                    for (int p = 0; p < 16; ++p)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) lds[(c4 + i - 64 * half) * PANEL_TLD + rr + 8 * p] = v[p][i];
                 }
-                store_split4_h2(uh, uh + ws.plane, rr + 8 * p, c4, x * su);
+                __syncthreads();
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int a = 64 * half + rr + 8 * p;
+                    const float* src = &lds[(rr + 8 * p) * PANEL_TLD + c4];
+                    const v4f x = {src[0], src[1], src[2], src[3]};
+                    *(KFAC_AS1 v4f*)&Uc[(size_t)a * NB + c4] = x;
+                    store_split4_h2(uh, uh + ws.plane, a, c4, x * su);
+                }
             }
         }
         __threadfence_block();
@@ -782,22 +792,28 @@ __global__ __launch_bounds__(256) void inv_panel_kernel(ChainBatch b) {
         tm = block_absmax(tm, red);                       // (its barriers also separate the product's LDS use from this one)
         const float st = panel_scale(tm);
         if (t == 0) ws.scaleT(q, slab) = st;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int nbk = 0; nbk < 2; ++nbk)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    lds[acc_row(wm, mb, r, lane) * PANEL_RLD + acc_col(wn, nbk, lane)] = acc.c[mb][nbk][r];
-        __syncthreads();
         const int c4 = (t & 31) * 4, rr = t >> 5;
         KFAC_AS1 unsigned char* th = ws.TH(q) + (size_t)slab * PRE_SLAB;
+#pragma unroll 1
+        for (int half = 0; half < 2; ++half) {
+            if (half == 1) __syncthreads();
+            if (wm == half) {
 #pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const int row = rr + 8 * p;
-            const v4f x = *(const v4f*)&lds[row * PANEL_RLD + c4];
-            if (row < rows) *(KFAC_AS1 v4f*)&Tc[(size_t)row * NB + c4] = x;
-            store_split4_h2(th, th + ws.plane, row, c4, x * -st);
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nbk = 0; nbk < 2; ++nbk)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            lds[(acc_row(wm, mb, r, lane) - 64 * half) * PANEL_RLD + acc_col(wn, nbk, lane)] = acc.c[mb][nbk][r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = 64 * half + rr + 8 * p;
+                const v4f x = *(const v4f*)&lds[(rr + 8 * p) * PANEL_RLD + c4];
+                if (row < rows) *(KFAC_AS1 v4f*)&Tc[(size_t)row * NB + c4] = x;
+                store_split4_h2(th, th + ws.plane, row, c4, x * -st);
+            }
         }
         return;
     }

@@ -523,8 +523,10 @@ def gpu_inverse(S, damping):
     return out.cpu().numpy(), int(info.item())
 
 
-# (block counts 1 .. 10: matrices that never, sometimes and mostly take their steps in pairs; ragged and full last blocks)
-@pytest.mark.parametrize("dim", [1, 2, 16, 64, 65, 128, 129, 148, 256, 257, 300, 384, 512, 513, 640, 769, 897, 1153])
+# (block counts 1 .. 13: every length of a matrix's last group of steps, after one, two and three full groups; ragged and
+# full last blocks)
+@pytest.mark.parametrize("dim", [1, 2, 16, 64, 65, 128, 129, 148, 256, 257, 300, 384, 512, 513, 640, 700, 769, 897, 1153,
+                                 1290, 1500, 1601])
 def test_damped_inverse_random_spd(dim):
     S = synth.random_spd(dim, seed=3, eig_lo=1e-3, eig_hi=10.0, n_zero=dim // 3)
     lam = float(np.float32(np.sqrt(1e-3)))
